@@ -1,0 +1,207 @@
+"""ctypes front end of the CPU oracle (oracle/pz_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
+It shares nothing with the HIP path and never imports it.  All arrays are numpy arrays on the
+host; bf16 tensors travel as uint16 bit patterns.
+
+Oracle cache layout: [num_slots][Hkv][d], slot = physical_page * P + offset (see pz_oracle.c).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pz_oracle.c")
+_LIB = os.path.join(_HERE, "libpz_oracle.so")
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "-shared", "-fPIC"]
+
+KV_FP8, KV_BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (rebuilds when the source is newer than the library)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm", "-lpthread"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        L.pzo_bf16_to_f32.restype = C.c_float
+        L.pzo_bf16_to_f32.argtypes = [C.c_uint16]
+        L.pzo_f32_to_bf16.restype = C.c_uint16
+        L.pzo_f32_to_bf16.argtypes = [C.c_float]
+        L.pzo_e4m3_decode.restype = C.c_float
+        L.pzo_e4m3_decode.argtypes = [C.c_uint8]
+        L.pzo_e4m3_encode.restype = C.c_uint8
+        L.pzo_e4m3_encode.argtypes = [C.c_float]
+        L.pzo_quantize.restype = C.c_uint8
+        L.pzo_quantize.argtypes = [C.c_uint16, C.c_float]
+        L.pzo_round_scale_up_pow2.restype = C.c_float
+        L.pzo_round_scale_up_pow2.argtypes = [C.c_float]
+        L.pzo_kv_append.restype = None
+        L.pzo_kv_append.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_float]
+        L.pzo_decode_attn.restype = None
+        L.pzo_decode_attn.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                      C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                      C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_int, C.c_int,
+                                      C.c_void_p, C.c_int64, C.c_void_p, C.c_int]
+        L.pzo_decode_attn_partials.restype = None
+        L.pzo_decode_attn_partials.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                               C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                               C.c_int, C.c_int, C.c_float, C.c_float, C.c_int,
+                                               C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                               C.c_int]
+        L.pzo_splitk_reduce.restype = None
+        L.pzo_splitk_reduce.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                        C.c_void_p, C.c_float, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _req(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+# ---------------------------------------------------------------- scalar codec helpers
+
+def e4m3_decode(codes) -> np.ndarray:
+    codes = np.asarray(codes, dtype=np.uint8)
+    f = lib().pzo_e4m3_decode
+    return np.array([f(int(c)) for c in codes.ravel()], dtype=np.float32).reshape(codes.shape)
+
+
+def e4m3_encode(x) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float32)
+    f = lib().pzo_e4m3_encode
+    return np.array([f(float(v)) for v in x.ravel()], dtype=np.uint8).reshape(x.shape)
+
+
+def quantize(x_bf16_bits, scale: float) -> np.ndarray:
+    x = np.asarray(x_bf16_bits, dtype=np.uint16)
+    f = lib().pzo_quantize
+    return np.array([f(int(v), float(scale)) for v in x.ravel()], dtype=np.uint8).reshape(x.shape)
+
+
+def bf16_to_f32(bits) -> np.ndarray:
+    bits = np.asarray(bits, dtype=np.uint16)
+    f = lib().pzo_bf16_to_f32
+    return np.array([f(int(v)) for v in bits.ravel()], dtype=np.float32).reshape(bits.shape)
+
+
+def f32_to_bf16(x) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float32)
+    f = lib().pzo_f32_to_bf16
+    return np.array([f(float(v)) for v in x.ravel()], dtype=np.uint16).reshape(x.shape)
+
+
+def round_scale_up_pow2(s: float) -> float:
+    return float(lib().pzo_round_scale_up_pow2(float(s)))
+
+
+# ---------------------------------------------------------------- cache + attention
+
+def new_cache(num_slots: int, Hkv: int, d: int, kv_dtype: int = KV_FP8, fill: int = 0xAA):
+    """K and V caches in the oracle layout, pre-filled with a canary byte."""
+    dt = np.uint8 if kv_dtype == KV_FP8 else np.uint16
+    fillv = fill if kv_dtype == KV_FP8 else (fill | (fill << 8))
+    k = np.full((num_slots, Hkv, d), fillv, dtype=dt)
+    v = np.full((num_slots, Hkv, d), fillv, dtype=dt)
+    return k, v
+
+
+def kv_append(k_cache, v_cache, k_new_bits, v_new_bits, slot_mapping, k_scale, v_scale):
+    """Quantise (or copy, for a bf16 cache) new K/V rows into the cache, in place."""
+    kv_dtype = KV_FP8 if k_cache.dtype == np.uint8 else KV_BF16
+    assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
+    _, Hkv, d = k_cache.shape
+    k_new = _req(k_new_bits, np.uint16)
+    v_new = _req(v_new_bits, np.uint16)
+    slots = _req(slot_mapping, np.int64)
+    T = slots.shape[0]
+    assert k_new.shape == (T, Hkv, d) and v_new.shape == (T, Hkv, d)
+    assert slots.max(initial=-1) < k_cache.shape[0]
+    lib().pzo_kv_append(_p(k_cache), _p(v_cache), kv_dtype, Hkv, d, _p(k_new), _p(v_new), _p(slots),
+                        T, float(k_scale), float(v_scale))
+
+
+def _check_tables(k_cache, P, block_table, seq_lens):
+    B, max_pages = block_table.shape
+    assert seq_lens.shape == (B,)
+    num_pages = k_cache.shape[0] // P
+    for b in range(B):
+        n = -(-int(seq_lens[b]) // P)
+        assert n <= max_pages
+        if n:
+            assert 0 <= block_table[b, :n].min() and block_table[b, :n].max() < num_pages
+
+
+def decode_attn(k_cache, v_cache, P, q_bits, block_table, seq_lens, sinks, sm_scale, k_scale,
+                v_scale, window=0, accum="f32", rows=None, nthreads=1) -> np.ndarray:
+    """Unsplit decode attention by the definition; returns fp32 [B][Hq][d].
+
+    rows: optional int array of b*Hq+h; other rows of the result stay zero."""
+    kv_dtype = KV_FP8 if k_cache.dtype == np.uint8 else KV_BF16
+    _, Hkv, d = k_cache.shape
+    q = _req(q_bits, np.uint16)
+    B, Hq, dq = q.shape
+    assert dq == d and Hq % Hkv == 0
+    bt = _req(block_table, np.int32)
+    sl = _req(seq_lens, np.int32)
+    _check_tables(k_cache, P, bt, sl)
+    sk = None if sinks is None else _req(sinks, np.float32)
+    out = np.zeros((B, Hq, d), dtype=np.float32)
+    r = None if rows is None else _req(rows, np.int32)
+    lib().pzo_decode_attn(_p(k_cache), _p(v_cache), kv_dtype, P, Hkv, d, _p(q), _p(bt), bt.shape[1],
+                          _p(sl), B, Hq, _p(sk), float(sm_scale), float(k_scale), float(v_scale),
+                          int(window), 0 if accum == "f32" else 1, _p(r),
+                          0 if r is None else r.shape[0], _p(out), int(nthreads))
+    return out
+
+
+def decode_attn_partials(k_cache, v_cache, P, q_bits, block_table, seq_lens, sm_scale, k_scale,
+                         window, split_tokens, n_splits, accum="f32", nthreads=1):
+    """Sink-free split-K partials by the chunked definition: (acc [B][Hq][S][d], ml [B][Hq][S][2])."""
+    kv_dtype = KV_FP8 if k_cache.dtype == np.uint8 else KV_BF16
+    _, Hkv, d = k_cache.shape
+    q = _req(q_bits, np.uint16)
+    B, Hq, _ = q.shape
+    bt = _req(block_table, np.int32)
+    sl = _req(seq_lens, np.int32)
+    _check_tables(k_cache, P, bt, sl)
+    acc = np.zeros((B, Hq, n_splits, d), dtype=np.float32)
+    ml = np.zeros((B, Hq, n_splits, 2), dtype=np.float32)
+    lib().pzo_decode_attn_partials(_p(k_cache), _p(v_cache), kv_dtype, P, Hkv, d, _p(q), _p(bt),
+                                   bt.shape[1], _p(sl), B, Hq, float(sm_scale), float(k_scale),
+                                   int(window), int(split_tokens), int(n_splits),
+                                   0 if accum == "f32" else 1, _p(acc), _p(ml), int(nthreads))
+    return acc, ml
+
+
+def splitk_reduce(part_acc, part_ml, sinks, v_scale) -> np.ndarray:
+    acc = _req(part_acc, np.float32)
+    ml = _req(part_ml, np.float32)
+    B, Hq, S, d = acc.shape
+    assert ml.shape == (B, Hq, S, 2)
+    sk = None if sinks is None else _req(sinks, np.float32)
+    out = np.zeros((B, Hq, d), dtype=np.float32)
+    lib().pzo_splitk_reduce(_p(acc), _p(ml), B, Hq, d, S, _p(sk), float(v_scale), _p(out))
+    return out

@@ -1,0 +1,63 @@
+"""Test-side helpers: an independent dense float64 reference and oracle cache construction.
+
+The dense reference below is written from the textbook definition of softmax attention with
+numpy/torch library routines (float8 decoding by torch.float8_e4m3fn, softmax by scipy); it
+shares no code with oracle/pz_oracle.c and is what pins it.
+"""
+import numpy as np
+import torch
+from scipy.special import logsumexp
+
+import oracle
+from workloads import Case, bf16_to_f32
+
+
+def torch_decode_e4m3(codes: np.ndarray) -> np.ndarray:
+    t = torch.from_numpy(np.ascontiguousarray(codes, dtype=np.uint8))
+    return t.view(torch.float8_e4m3fn).to(torch.float64).numpy()
+
+
+def oracle_cache(case: Case, kv_dtype=oracle.KV_FP8, upto=None):
+    """Oracle-layout caches filled by the oracle's own append from the case's bf16 K/V."""
+    kc, vc = oracle.new_cache(case.num_pages * case.P, case.Hkv, case.d, kv_dtype)
+    n = len(case.slot_mapping) if upto is None else upto
+    oracle.kv_append(kc, vc, case.k[:n], case.v[:n], case.slot_mapping[:n], case.k_scale, case.v_scale)
+    return kc, vc
+
+
+def dense_reference(case: Case, kc, vc, window=None, sinks="case", sm_scale=None, k_scale=None,
+                    v_scale=None, seq_lens=None):
+    """float64 softmax attention over the dequantised cache, dense, one (b, h) at a time."""
+    window = case.window if window is None else window
+    sinks = case.sinks if isinstance(sinks, str) else sinks
+    sm_scale = case.sm_scale if sm_scale is None else sm_scale
+    k_scale = case.k_scale if k_scale is None else k_scale
+    v_scale = case.v_scale if v_scale is None else v_scale
+    seq_lens = case.seq_lens if seq_lens is None else seq_lens
+    G = case.Hq // case.Hkv
+    dec = torch_decode_e4m3 if kc.dtype == np.uint8 else (lambda b: bf16_to_f32(b).astype(np.float64))
+    q = bf16_to_f32(case.q).astype(np.float64)
+    out = np.zeros((case.B, case.Hq, case.d))
+    for b in range(case.B):
+        L = int(seq_lens[b])
+        if L == 0:
+            continue
+        lo = L - window if (window > 0 and L > window) else 0
+        j = np.arange(lo, L)
+        slots = case.block_table[b, j // case.P].astype(np.int64) * case.P + j % case.P
+        for h in range(case.Hq):
+            g = h // G
+            K = dec(kc[slots, g, :]) * k_scale            # [n][d]
+            V = dec(vc[slots, g, :]) * v_scale
+            s = sm_scale * (K @ q[b, h])
+            logits = s if sinks is None else np.concatenate([s, [float(sinks[h])]])
+            p = np.exp(logits - logsumexp(logits))
+            out[b, h] = p[:len(s)] @ V
+    return out
+
+
+def rel_err(got, want):
+    """max-abs error relative to the RMS of the reference output (the parity metric)."""
+    want = np.asarray(want, dtype=np.float64)
+    rms = np.sqrt(np.mean(want ** 2))
+    return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - want)) / (rms if rms > 0 else 1.0))

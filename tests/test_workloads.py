@@ -1,0 +1,71 @@
+"""Input-recipe checks: layer pattern, byte accounting, paging tables (CPU only).
+
+Facts pinned to the paper: the parent alternates window-128 and full-attention layers (18 of
+each over 36 layers) and 8 of the 18 full layers become window-8192 layers (Section 2, "Window
+attention for long-context inference"); the resulting KV cache is about 40 % smaller at the
+64K-input/64K-output scenario (Section 2, "Optimized Scenarios"); FP8 KV doubles the token
+capacity of the cache (Section 3, "KV Quantization").
+"""
+import numpy as np
+
+import workloads as wl
+
+
+def test_layer_pattern_counts():
+    pat = wl.layer_pattern()
+    assert len(pat) == 36
+    assert pat.count(128) == 18 and pat.count(8192) == 8 and pat.count(0) == 10
+    assert all(w == 128 for w in pat[0::2]) and all(w in (0, 8192) for w in pat[1::2])
+    assert pat == wl.layer_pattern()                          # seeded, reproducible
+    parent = wl.layer_pattern(n_converted=0)
+    assert parent.count(128) == 18 and parent.count(0) == 18
+
+
+def test_kv_cache_is_about_forty_percent_smaller():
+    L = 131072                                                # 64K input + 64K output
+    child = sum(wl.kv_tokens_read([L], w) for w in wl.layer_pattern())
+    parent = sum(wl.kv_tokens_read([L], w) for w in wl.layer_pattern(n_converted=0))
+    assert child == 10 * L + 8 * 8192 + 18 * 128 and parent == 18 * L + 18 * 128
+    assert abs(child / parent - 0.5837) < 1e-3                # 41.6 % smaller: the paper's "40 %"
+    assert 0.38 < 1 - child / parent < 0.44
+    lens = wl.ragged_lengths(5, 32, 1024, 131072)
+    r = (sum(wl.kv_tokens_read(lens, w) for w in wl.layer_pattern())
+         / sum(wl.kv_tokens_read(lens, w) for w in wl.layer_pattern(n_converted=0)))
+    assert 0.55 < r < 0.66
+
+
+def test_bytes_per_cached_token():
+    assert wl.kv_bytes_per_token(8, 64, 1) == 1024 and wl.kv_bytes_per_token(8, 64, 2) == 2048
+    assert wl.kv_tokens_read([100, 5000, 9000], 8192) == 100 + 5000 + 8192
+    assert wl.kv_tokens_read([100, 5000, 9000], 0) == 14100
+
+
+def test_paged_tables_are_a_partial_permutation():
+    case = wl.make_case("t", B=4, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37, 1, 16], seed=3)
+    used = case.block_table[case.block_table >= 0]
+    assert len(used) == len(set(used.tolist())) == 7 + 3 + 1 + 1
+    assert used.max() < case.num_pages and case.num_pages == len(used) + 2
+    assert len(set(case.slot_mapping.tolist())) == 154
+    off = case.offsets
+    for b in range(4):
+        j = np.arange(int(case.seq_lens[b]))
+        want = case.block_table[b, j // 16].astype(np.int64) * 16 + j % 16
+        assert np.array_equal(case.slot_mapping[off[b]:off[b + 1]], want)
+
+
+def test_scales_are_amax_over_448_and_below_one():
+    for case in (wl.config1_tiny(), wl.make_case("o", B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[64, 64],
+                                                 outlier_frac=0.05, seed=1)):
+        for bits, s in ((case.k, case.k_scale), (case.v, case.v_scale)):
+            amax = np.max(np.abs(wl.bf16_to_f32(bits)))
+            assert s == float(np.float32(amax) / np.float32(448)) and 0 < s < 1
+    p2 = wl.make_case("p", B=1, Hq=8, Hkv=2, d=64, P=16, seq_lens=[64], pow2_scales=True)
+    raw = wl.make_case("p", B=1, Hq=8, Hkv=2, d=64, P=16, seq_lens=[64])
+    for s, r in ((p2.k_scale, raw.k_scale), (p2.v_scale, raw.v_scale)):
+        assert np.log2(s) == int(np.log2(s)) and r <= s < 2 * r and s <= 1
+
+
+def test_outlier_channels_raise_the_k_scale():
+    a = wl.make_case("a", B=1, Hq=8, Hkv=2, d=64, P=16, seq_lens=[256], seed=9)
+    b = wl.make_case("b", B=1, Hq=8, Hkv=2, d=64, P=16, seq_lens=[256], seed=9, outlier_frac=0.05)
+    assert len(b.extra["outlier_pairs"]) == 6 and b.k_scale > 5 * a.k_scale

@@ -1,0 +1,187 @@
+"""Seeded synthetic inputs for the decode-attention path (shared by tests, bench and smoke).
+
+This module only *generates inputs*: random tensors, ragged lengths, block tables, slot
+mappings, the layer pattern.  It holds none of the method's arithmetic (no FP8 codec, no
+attention) and imports neither the oracle nor the HIP binding.  bf16 tensors are carried as
+uint16 bit patterns so that the oracle and the GPU path receive the same bytes.
+
+Shapes follow the gpt-oss attention geometry the paper's serving scenarios run on (64 query
+heads, 8 KV heads, head_dim 64; alternating window-128 / full layers, 8 of the 18 full layers
+turned into window-8192 -- paper Section 2, "Window attention for long-context inference").
+The paper's activations come from a real model on its own dataset; N(0,1) data stands in.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+E4M3_MAX = 448.0
+
+
+# ------------------------------------------------------------------ bf16 plumbing
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = ((u >> 16) & 1) + np.uint32(0x7FFF)
+    return ((u + r) >> 16).astype(np.uint16)
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def amax_scale(bits: np.ndarray) -> float:
+    """Max-calibrated per-tensor scale of the configs: amax / 448, one fp32 divide."""
+    amax = np.float32(np.max(np.abs(bf16_to_f32(bits)))) if bits.size else np.float32(0.0)
+    s = np.float32(amax) / np.float32(E4M3_MAX)
+    return float(s) if s > 0 else 1.0
+
+
+# ------------------------------------------------------------------ a decode-attention case
+
+@dataclass
+class Case:
+    name: str
+    B: int
+    Hq: int
+    Hkv: int
+    d: int
+    P: int
+    window: int
+    sm_scale: float
+    seq_lens: np.ndarray                 # int32 [B], includes the token appended this step
+    q: np.ndarray                        # uint16 [B][Hq][d]
+    k: np.ndarray                        # uint16 [sum L][Hkv][d], sequences concatenated
+    v: np.ndarray                        # uint16 [sum L][Hkv][d]
+    sinks: Optional[np.ndarray]          # fp32 [Hq] or None
+    k_scale: float
+    v_scale: float
+    num_pages: int
+    block_table: np.ndarray              # int32 [B][max_pages]
+    slot_mapping: np.ndarray             # int64 [sum L]: slot of every context token
+    split_tokens: int = 0
+    extra: dict = field(default_factory=dict)
+
+    @property
+    def max_pages(self) -> int:
+        return int(self.block_table.shape[1])
+
+    @property
+    def offsets(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(self.seq_lens.astype(np.int64))])
+
+
+def paged_tables(rng: np.random.Generator, seq_lens: np.ndarray, P: int, spare_pages: int = 2,
+                 min_max_pages: int = 1):
+    """Random page assignment: a permutation of the physical pages, dealt to the sequences.
+
+    Returns (num_pages, block_table int32 [B][max_pages], slot_mapping int64 [sum L]).
+    Unused block-table entries hold -1; `spare_pages` pages belong to no sequence."""
+    seq_lens = np.asarray(seq_lens, dtype=np.int64)
+    n_pages = (seq_lens + P - 1) // P
+    total = int(n_pages.sum())
+    num_pages = total + spare_pages
+    perm = rng.permutation(num_pages).astype(np.int32)
+    max_pages = max(int(n_pages.max(initial=0)), min_max_pages)
+    bt = np.full((len(seq_lens), max_pages), -1, dtype=np.int32)
+    slots = np.empty(int(seq_lens.sum()), dtype=np.int64)
+    at, tok = 0, 0
+    for b, L in enumerate(seq_lens):
+        n = int(n_pages[b])
+        bt[b, :n] = perm[at:at + n]
+        at += n
+        j = np.arange(int(L), dtype=np.int64)
+        slots[tok:tok + int(L)] = bt[b, j // P].astype(np.int64) * P + j % P
+        tok += int(L)
+    return num_pages, bt, slots
+
+
+def make_case(name: str, *, B: int, Hq: int, Hkv: int, d: int, P: int, seq_lens, window: int = 0,
+              seed: int = 0, sinks: bool = True, sm_scale: Optional[float] = None,
+              split_tokens: int = 0, outlier_frac: float = 0.0, outlier_gain: float = 20.0,
+              pow2_scales: bool = False, unit_scales: bool = False) -> Case:
+    """q, k, v ~ N(0,1) rounded to bf16; sinks ~ N(0,1) fp32; scales = amax/448 per tensor.
+
+    outlier_frac > 0 multiplies round(outlier_frac * Hkv * d) seeded (kv-head, channel) pairs of
+    K by `outlier_gain` for every token before calibration (outlier channels)."""
+    rng = np.random.default_rng(seed)
+    seq_lens = np.asarray(seq_lens, dtype=np.int32)
+    assert seq_lens.shape == (B,)
+    T = int(seq_lens.astype(np.int64).sum())
+    q = rng.standard_normal((B, Hq, d), dtype=np.float32)
+    k = rng.standard_normal((T, Hkv, d), dtype=np.float32)
+    v = rng.standard_normal((T, Hkv, d), dtype=np.float32)
+    extra = {}
+    if outlier_frac > 0:
+        n_out = int(round(outlier_frac * Hkv * d))
+        pairs = rng.choice(Hkv * d, size=n_out, replace=False)
+        k.reshape(T, Hkv * d)[:, pairs] *= np.float32(outlier_gain)
+        extra["outlier_pairs"] = pairs
+    sk = rng.standard_normal(Hq).astype(np.float32) if sinks else None
+    qb, kb, vb = bf16_bits(q), bf16_bits(k), bf16_bits(v)
+    k_scale, v_scale = amax_scale(kb), amax_scale(vb)
+    if pow2_scales:                       # exact: frexp/ldexp only
+        def up(s):
+            m, e = np.frexp(np.float32(s))
+            return float(s) if m == 0.5 else float(np.ldexp(np.float32(1.0), e))
+        k_scale, v_scale = up(k_scale), up(v_scale)
+    if unit_scales:
+        k_scale = v_scale = 1.0
+    num_pages, bt, slots = paged_tables(rng, seq_lens, P)
+    return Case(name=name, B=B, Hq=Hq, Hkv=Hkv, d=d, P=P, window=window,
+                sm_scale=float(sm_scale if sm_scale is not None else 1.0 / np.sqrt(d)),
+                seq_lens=seq_lens, q=qb, k=kb, v=vb, sinks=sk, k_scale=k_scale, v_scale=v_scale,
+                num_pages=num_pages, block_table=bt, slot_mapping=slots, split_tokens=split_tokens,
+                extra=extra)
+
+
+# ------------------------------------------------------------------ the benchmark configurations
+
+def config1_tiny(seed: int = 0) -> Case:
+    """Tiny oracle case: batch 2, 8 q / 2 KV heads, d 64, contexts 100 and 37, page size 16."""
+    return make_case("cfg1_tiny", B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37], seed=seed,
+                     sm_scale=1.0 / 8.0)
+
+
+def config2_full(seed: int = 2, B: int = 64, L: int = 8192) -> Case:
+    """gpt-oss-shaped full-attention layer, every sequence at context L, page size 64."""
+    return make_case("cfg2_full", B=B, Hq=64, Hkv=8, d=64, P=64, seq_lens=[L] * B, seed=seed)
+
+
+def config3_long(seed: int = 3, B: int = 16, L: int = 65536, split_tokens: int = 1024) -> Case:
+    """Long-context split-K layer with 1 % outlier K channels (x20) before calibration."""
+    return make_case("cfg3_long", B=B, Hq=64, Hkv=8, d=64, P=64, seq_lens=[L] * B, seed=seed,
+                     split_tokens=split_tokens, outlier_frac=0.01)
+
+
+def ragged_lengths(seed: int, B: int, lo: int, hi: int) -> np.ndarray:
+    return np.random.default_rng(seed).integers(lo, hi + 1, size=B).astype(np.int32)
+
+
+def config4_window(seed: int = 4, B: int = 256, window: int = 128, lo: int = 1024,
+                   hi: int = 65536) -> Case:
+    """Sliding-window layer over ragged contexts uniform in [lo, hi]."""
+    return make_case("cfg4_window%d" % window, B=B, Hq=64, Hkv=8, d=64, P=64,
+                     seq_lens=ragged_lengths(seed, B, lo, hi), window=window, seed=seed)
+
+
+def layer_pattern(seed: int = 5, n_layers: int = 36, n_converted: int = 8) -> list:
+    """Per-layer window of the heterogeneous model: even layers window 128, odd layers full,
+    and `n_converted` seeded odd layers turned into window 8192 (0 = full attention)."""
+    full_layers = [i for i in range(n_layers) if i % 2 == 1]
+    conv = set(np.random.default_rng(seed).choice(full_layers, size=n_converted, replace=False).tolist())
+    return [128 if i % 2 == 0 else (8192 if i in conv else 0) for i in range(n_layers)]
+
+
+def kv_tokens_read(seq_lens, window: int) -> int:
+    """Number of cached tokens one layer's attention reads: sum_b min(L_b, W or inf)."""
+    L = np.asarray(seq_lens, dtype=np.int64)
+    return int((np.minimum(L, window) if window > 0 else L).sum())
+
+
+def kv_bytes_per_token(Hkv: int = 8, d: int = 64, elem_bytes: int = 1) -> int:
+    """K and V bytes of one cached token of one layer."""
+    return 2 * Hkv * d * elem_bytes
