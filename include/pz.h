@@ -1,0 +1,165 @@
+/*
+ * pz.h -- C ABI of the MI355X (gfx950) decode-attention library.
+ *
+ * The library implements the part of a decode step whose cost the paper's inference
+ * optimisations act on: single-token grouped-query attention over a paged KV cache that is
+ * stored in FP8 (E4M3) with one calibrated K scale and one V scale per layer (paper Section 3,
+ * "KV Quantization"), where each layer is either full-context or sliding-window attention
+ * (Section 2, "Window attention for long-context inference"), plus the kernel that quantises
+ * and appends the new token's K/V to that cache.  Learned per-head attention-sink logits (a
+ * property of the gpt-oss parent model) take part in the softmax denominator.
+ *
+ * Conventions that hold for every entry point:
+ *   - Every pointer is a DEVICE pointer unless marked "host".  The pz_cache descriptor itself
+ *     is a host struct (its k / v members are device pointers).
+ *   - The caller owns every buffer.  The library never allocates, frees or synchronises; each
+ *     call only enqueues kernels on `hip_stream` (a hipStream_t, NULL = the default stream) and
+ *     returns.  Buffers must stay alive until the stream has run past the call.
+ *   - Argument errors are detected on the host before anything is enqueued and are reported
+ *     through the return value (never abort, never throw).  A failed launch gives
+ *     PZ_ERR_LAUNCH.  Out-of-range block-table entries or slots are the caller's bug and are
+ *     not detected.
+ *   - Supported shapes: head_dim == 64; page_size in {16, 32, 64}; n_q_heads a multiple of
+ *     n_kv_heads with group size n_q_heads / n_kv_heads <= 8.
+ *
+ * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
+ * discuss paging):
+ *     K : [num_pages][n_kv_heads][page_size][head_dim]     (a token's channels are contiguous)
+ *     V : [num_pages][n_kv_heads][head_dim][page_size]     (a channel's tokens are contiguous)
+ *   element = 1 byte OCP FP8 E4M3 (PZ_KV_FP8_E4M3) or 2 bytes bf16 (PZ_KV_BF16).
+ *   A "slot" is physical_page * page_size + offset_in_page.
+ */
+#ifndef PZ_H
+#define PZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PZ_OK = 0,
+    PZ_ERR_NULL = -1,         /* a required pointer is NULL */
+    PZ_ERR_SHAPE = -2,        /* negative / inconsistent sizes */
+    PZ_ERR_UNSUPPORTED = -3,  /* valid request outside the supported set above */
+    PZ_ERR_WORKSPACE = -4,    /* workspace missing or too small */
+    PZ_ERR_LAUNCH = -5        /* the HIP runtime refused the launch */
+} pz_status;
+
+typedef enum { PZ_KV_FP8_E4M3 = 0, PZ_KV_BF16 = 1 } pz_kv_dtype;
+typedef enum { PZ_OUT_F32 = 0, PZ_OUT_BF16 = 1 } pz_out_dtype;
+
+typedef struct {
+    void *k;                  /* device, layout above */
+    void *v;                  /* device, layout above */
+    int32_t num_pages;
+    int32_t page_size;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;            /* pz_kv_dtype */
+} pz_cache;
+
+/* Human-readable name of a status code (host string, static storage). */
+const char *pz_status_string(pz_status s);
+
+/*
+ * Quantise-and-append (paper Section 3, "KV Quantization": FP8 KV cache with per-layer scales).
+ *
+ * For every token t < n_tokens with slot = slot_mapping[t] >= 0, every KV head g and channel c:
+ *     K[slot][g][c] = e4m3( float(k_new[t][g][c]) / k_scale )       (same for V with v_scale)
+ * where e4m3() rounds to nearest even and saturates at +-448 (NaN stays NaN), and the division
+ * is one IEEE fp32 division.  Tokens with a negative slot are skipped; all other cache bytes are
+ * left untouched.  With cache->dtype == PZ_KV_BF16 the bf16 values are copied through unscaled
+ * (comparison variant; the scales are ignored).
+ *
+ *   k_new, v_new  : bf16 [n_tokens][n_kv_heads][head_dim], contiguous
+ *   slot_mapping  : int64 [n_tokens]
+ *   k_scale, v_scale : > 0 (a scale of 1 is the paper's "no scales" variant; powers of two are
+ *                      its final choice -- the library takes any positive value)
+ * n_tokens == 0 is legal and enqueues nothing.  Two tokens with the same slot race.
+ */
+pz_status pz_kv_append_fp8(const pz_cache *cache /* host */, const void *k_new, const void *v_new,
+                           const int64_t *slot_mapping, int64_t n_tokens, float k_scale,
+                           float v_scale, void *hip_stream);
+
+/*
+ * Number of split-K chunks that cover every sequence of a call (host arithmetic only).
+ * Chunk i of sequence b covers the logical positions
+ *     [a_b + i*split_tokens, a_b + (i+1)*split_tokens)  intersected with  [lo_b, L_b),
+ * lo_b = max(0, L_b - window) for window > 0, else 0;  a_b = lo_b rounded down to a multiple of
+ * 64.  The result is ceil(span / split_tokens) with span = max_seq_len for full attention and
+ * min(max_seq_len, window + 63) for window layers.  Returns 0 for invalid arguments.
+ */
+int32_t pz_decode_attn_n_splits(int32_t max_seq_len, int32_t window, int32_t split_tokens);
+
+/*
+ * Bytes of split-K workspace for a call:  batch * n_q_heads * n_splits * (head_dim + 2) * 4.
+ * Layout: float acc[batch][n_q_heads][n_splits][head_dim], then
+ *         float ml [batch][n_q_heads][n_splits][2]  = (m, l).
+ * A partial is sink-free and unnormalised:  with s_j the scaled logit of position j,
+ *     m = max_j s_j (natural-log units),  l = sum_j exp(s_j - m),
+ *     acc[c] = sum_j exp(s_j - m) * decode(V[j][c])        (v_scale not applied),
+ * an empty chunk is (m = -inf, l = 0, acc = 0).
+ */
+size_t pz_decode_attn_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim,
+                                      int32_t n_splits);
+
+/*
+ * Single-token decode attention over the paged cache (the operation whose KV-cache traffic
+ * dominates long-context decoding, paper Section 2 "Optimized Scenarios"; window rule from
+ * Section 2 "Window attention for long-context inference": a token attends to the most recent
+ * `window` positions, its own just-appended position included).
+ *
+ * For every sequence b < batch and query head h (KV head g = h / (n_q_heads / n_kv_heads)), over
+ * the positions j in [lo_b, L_b):
+ *     s_j  = (sm_scale * k_scale) * sum_c q[b][h][c] * decode(K[j][g][c])
+ *     M    = max(sink_h, max_j s_j),   D = exp(sink_h - M) + sum_j exp(s_j - M)
+ *     out[b][h][c] = v_scale * sum_j exp(s_j - M) * decode(V[j][g][c]) / D
+ * The sink logit is in the units of s_j, joins the maximum and the denominator and has no value
+ * row; sinks == NULL means no sink (plain softmax).  L_b == 0 gives a zero row.
+ *
+ *   q            : bf16 [batch][n_q_heads][head_dim]
+ *   block_table  : int32 [batch][max_pages_per_seq]; entry p of row b is the physical page of
+ *                  positions [p*page_size, (p+1)*page_size); only entries that hold attended
+ *                  positions are read
+ *   seq_lens     : int32 [batch], L_b, counting the token appended in this step
+ *   sinks        : fp32 [n_q_heads] or NULL
+ *   sm_scale, k_scale, v_scale : > 0
+ *   window       : 0 = full attention, else sliding window length
+ *   split_tokens : 0 = single pass: the sink is applied and `out` is written
+ *                  (workspace may be NULL, n_splits is ignored);
+ *                  > 0 (a multiple of 64) = split-K: only the partials of the n_splits chunks
+ *                  defined at pz_decode_attn_n_splits are written to `workspace`, `out` is not
+ *                  touched, and the caller enqueues pz_decode_attn_splitk_reduce on the same
+ *                  stream.  Positions beyond n_splits * split_tokens of a_b are ignored, so
+ *                  n_splits must be at least pz_decode_attn_n_splits(max_b L_b, ...).
+ *   out          : [batch][n_q_heads][head_dim], fp32 or bf16 (round to nearest even)
+ */
+pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
+                         const int32_t *block_table, int32_t max_pages_per_seq,
+                         const int32_t *seq_lens, int32_t batch, int32_t n_q_heads,
+                         const float *sinks, float sm_scale, float k_scale, float v_scale,
+                         int32_t window, int32_t split_tokens, int32_t n_splits, void *workspace,
+                         size_t workspace_bytes, void *out, int32_t out_dtype, void *hip_stream);
+
+/*
+ * Second pass of split-K: log-sum-exp merge of the partials, sink, normalisation.
+ *     M = max(sink_h, max_i m_i);  D = exp(sink_h - M) + sum_i l_i exp(m_i - M)
+ *     out[b][h][c] = v_scale * sum_i acc_i[c] exp(m_i - M) / D
+ * Empty partials (m = -inf) contribute nothing; a row whose partials are all empty is 0 (also
+ * without a sink -- never NaN).  seq_lens / window / split_tokens, when seq_lens != NULL, only
+ * bound how many leading chunks of each row are read (the others are empty by construction);
+ * with seq_lens == NULL all n_splits partials are read.
+ */
+pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_bytes, int32_t batch,
+                                       int32_t n_q_heads, int32_t head_dim, int32_t n_splits,
+                                       const int32_t *seq_lens, int32_t window,
+                                       int32_t split_tokens, const float *sinks, float v_scale,
+                                       void *out, int32_t out_dtype, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PZ_H */

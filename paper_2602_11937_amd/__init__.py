@@ -1,0 +1,13 @@
+"""MI355X-native FP8-KV decode attention: thin Python binding of the C-ABI library libpz.so.
+
+Every step of the path runs in the HIP kernels behind the C ABI declared in include/pz.h; this
+package only marshals arguments (torch tensors supply device memory and streams).  There is no
+CPU fallback: if the library has not been built, importing `binding` functions raises.
+"""
+from .binding import (KV_BF16, KV_FP8, OUT_BF16, OUT_F32, PagedCache, PzError, lib, lib_path,
+                      pz_decode_attn, pz_decode_attn_n_splits, pz_decode_attn_splitk_reduce,
+                      pz_decode_attn_workspace_bytes, pz_kv_append_fp8, pz_status_string)
+
+__all__ = ["KV_BF16", "KV_FP8", "OUT_BF16", "OUT_F32", "PagedCache", "PzError", "lib", "lib_path",
+           "pz_decode_attn", "pz_decode_attn_n_splits", "pz_decode_attn_splitk_reduce",
+           "pz_decode_attn_workspace_bytes", "pz_kv_append_fp8", "pz_status_string"]

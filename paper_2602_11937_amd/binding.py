@@ -1,0 +1,162 @@
+"""ctypes binding of libpz.so: same names as the C entry points, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+KV_FP8, KV_BF16 = 0, 1
+OUT_F32, OUT_BF16 = 0, 1
+
+
+class PzError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, pz_status_string(status)))
+
+
+class _CCache(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("num_pages", C.c_int32),
+                ("page_size", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "libpz.so")
+
+
+_lib = None
+
+
+def lib():
+    """Load libpz.so (built by paper_2602_11937_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise ImportError("libpz.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                              "(there is no CPU fallback for the decode-attention path)")
+        L = C.CDLL(path)
+        L.pz_status_string.restype = C.c_char_p
+        L.pz_status_string.argtypes = [C.c_int]
+        L.pz_kv_append_fp8.restype = C.c_int
+        L.pz_kv_append_fp8.argtypes = [C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                       C.c_float, C.c_float, C.c_void_p]
+        L.pz_decode_attn_n_splits.restype = C.c_int32
+        L.pz_decode_attn_n_splits.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.pz_decode_attn_workspace_bytes.restype = C.c_size_t
+        L.pz_decode_attn_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+        L.pz_decode_attn.restype = C.c_int
+        L.pz_decode_attn.argtypes = [C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                     C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_float, C.c_float,
+                                     C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                     C.c_int32, C.c_void_p]
+        L.pz_decode_attn_splitk_reduce.restype = C.c_int
+        L.pz_decode_attn_splitk_reduce.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32,
+                                                   C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                                   C.c_float, C.c_void_p, C.c_int32, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def pz_status_string(status: int) -> str:
+    return lib().pz_status_string(int(status)).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or raw) address of a torch tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+@dataclass
+class PagedCache:
+    """Device K/V cache in the library's layout (K: [page][head][P][d], V: [page][head][d][P])."""
+    k: object
+    v: object
+    num_pages: int
+    page_size: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: int = KV_FP8
+
+    @staticmethod
+    def allocate(num_pages, page_size, n_kv_heads, head_dim, dtype=KV_FP8, device="cuda", fill=None):
+        import torch
+        tdt = torch.uint8 if dtype == KV_FP8 else torch.int16
+        k = torch.empty((num_pages, n_kv_heads, page_size, head_dim), dtype=tdt, device=device)
+        v = torch.empty((num_pages, n_kv_heads, head_dim, page_size), dtype=tdt, device=device)
+        if fill is not None:
+            k.fill_(fill)
+            v.fill_(fill)
+        return PagedCache(k, v, num_pages, page_size, n_kv_heads, head_dim, dtype)
+
+    def c_struct(self) -> _CCache:
+        return _CCache(_ptr(self.k), _ptr(self.v), self.num_pages, self.page_size, self.n_kv_heads,
+                       self.head_dim, self.dtype)
+
+
+def _cache_ref(cache):
+    if cache is None:
+        return None
+    return C.byref(cache.c_struct() if isinstance(cache, PagedCache) else cache)
+
+
+def pz_kv_append_fp8(cache, k_new, v_new, slot_mapping, n_tokens, k_scale, v_scale, stream=None,
+                     check=True) -> int:
+    st = lib().pz_kv_append_fp8(_cache_ref(cache), _ptr(k_new), _ptr(v_new), _ptr(slot_mapping),
+                                int(n_tokens), float(k_scale), float(v_scale), _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_kv_append_fp8")
+    return st
+
+
+def pz_decode_attn_n_splits(max_seq_len, window, split_tokens) -> int:
+    return int(lib().pz_decode_attn_n_splits(int(max_seq_len), int(window), int(split_tokens)))
+
+
+def pz_decode_attn_workspace_bytes(batch, n_q_heads, head_dim, n_splits) -> int:
+    return int(lib().pz_decode_attn_workspace_bytes(int(batch), int(n_q_heads), int(head_dim), int(n_splits)))
+
+
+def pz_decode_attn(cache, q, block_table, max_pages_per_seq, seq_lens, batch, n_q_heads, sinks, sm_scale,
+                   k_scale, v_scale, window, split_tokens, n_splits, workspace, workspace_bytes, out,
+                   out_dtype=OUT_F32, stream=None, check=True) -> int:
+    st = lib().pz_decode_attn(_cache_ref(cache), _ptr(q), _ptr(block_table), int(max_pages_per_seq),
+                              _ptr(seq_lens), int(batch), int(n_q_heads), _ptr(sinks), float(sm_scale),
+                              float(k_scale), float(v_scale), int(window), int(split_tokens), int(n_splits),
+                              _ptr(workspace), int(workspace_bytes), _ptr(out), int(out_dtype),
+                              _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_decode_attn")
+    return st
+
+
+def pz_decode_attn_splitk_reduce(workspace, workspace_bytes, batch, n_q_heads, head_dim, n_splits, seq_lens,
+                                 window, split_tokens, sinks, v_scale, out, out_dtype=OUT_F32, stream=None,
+                                 check=True) -> int:
+    st = lib().pz_decode_attn_splitk_reduce(_ptr(workspace), int(workspace_bytes), int(batch), int(n_q_heads),
+                                            int(head_dim), int(n_splits), _ptr(seq_lens), int(window),
+                                            int(split_tokens), _ptr(sinks), float(v_scale), _ptr(out),
+                                            int(out_dtype), _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_decode_attn_splitk_reduce")
+    return st

@@ -1,0 +1,201 @@
+// C-ABI layer: argument validation (host only, before anything is enqueued) and dispatch.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdlib.h>
+
+#include "pz.h"
+#include "pz_internal.h"
+
+namespace {
+
+bool supported_page(int p) { return p == 16 || p == 32 || p == 64; }
+
+pz_status check_cache(const pz_cache *c) {
+    if (c == nullptr || c->k == nullptr || c->v == nullptr) return PZ_ERR_NULL;
+    if (c->num_pages <= 0 || c->page_size <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0) return PZ_ERR_SHAPE;
+    if (c->dtype != PZ_KV_FP8_E4M3 && c->dtype != PZ_KV_BF16) return PZ_ERR_UNSUPPORTED;
+    if (c->head_dim != 64 || !supported_page(c->page_size)) return PZ_ERR_UNSUPPORTED;
+    return PZ_OK;
+}
+
+bool positive_finite(float x) { return x > 0.0f && isfinite(x); }
+
+int env_int(const char *name, int fallback) {
+    const char *s = getenv(name);
+    if (s == nullptr || *s == 0) return fallback;
+    const int v = atoi(s);
+    return v > 0 ? v : fallback;
+}
+
+int round_down_pow2(int x) {
+    int r = 1;
+    while (2 * r <= x) r *= 2;
+    return r;
+}
+
+// waves per workgroup: the steps of one (sequence, KV head[, chunk]) are dealt to the waves
+int pick_waves(int batch, int n_kv_heads, int max_steps, int n_chunks) {
+    const int forced = env_int("PZ_ATTN_WAVES", 0);
+    if (forced > 0) return forced > 8 ? 8 : round_down_pow2(forced);
+    const long groups = (long)batch * n_kv_heads * n_chunks;
+    int w = 1;
+    // aim at >= 4096 waves in flight (256 CUs x 4 SIMDs x 4) while keeping >= 2 steps per wave
+    while (w < 8 && groups * w < 4096 && max_steps >= 4 * w) w *= 2;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pz_status_string(pz_status s) {
+    switch (s) {
+        case PZ_OK: return "PZ_OK";
+        case PZ_ERR_NULL: return "PZ_ERR_NULL: a required pointer is NULL";
+        case PZ_ERR_SHAPE: return "PZ_ERR_SHAPE: negative or inconsistent sizes";
+        case PZ_ERR_UNSUPPORTED: return "PZ_ERR_UNSUPPORTED: outside the supported shapes/dtypes";
+        case PZ_ERR_WORKSPACE: return "PZ_ERR_WORKSPACE: workspace missing or too small";
+        case PZ_ERR_LAUNCH: return "PZ_ERR_LAUNCH: the HIP runtime refused the launch";
+    }
+    return "unknown pz_status";
+}
+
+pz_status pz_kv_append_fp8(const pz_cache *cache, const void *k_new, const void *v_new,
+                           const int64_t *slot_mapping, int64_t n_tokens, float k_scale,
+                           float v_scale, void *hip_stream) {
+    const pz_status cs = check_cache(cache);
+    if (cs != PZ_OK) return cs;
+    if (n_tokens < 0) return PZ_ERR_SHAPE;
+    if (n_tokens == 0) return PZ_OK;
+    if (k_new == nullptr || v_new == nullptr || slot_mapping == nullptr) return PZ_ERR_NULL;
+    if (cache->n_kv_heads > 65535) return PZ_ERR_UNSUPPORTED;
+    if (cache->dtype == PZ_KV_FP8_E4M3 && (!positive_finite(k_scale) || !positive_finite(v_scale)))
+        return PZ_ERR_SHAPE;
+    pz::AppendParams p;
+    p.k = static_cast<uint8_t *>(cache->k);
+    p.v = static_cast<uint8_t *>(cache->v);
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.slot_mapping = slot_mapping;
+    p.T = n_tokens;
+    p.Hkv = cache->n_kv_heads;
+    p.P = cache->page_size;
+    p.k_scale = k_scale;
+    p.v_scale = v_scale;
+    const hipError_t e = pz::launch_kv_append(p, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
+                                              static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
+int32_t pz_decode_attn_n_splits(int32_t max_seq_len, int32_t window, int32_t split_tokens) {
+    if (max_seq_len < 0 || window < 0 || split_tokens <= 0 || split_tokens % 64 != 0) return 0;
+    int64_t span = max_seq_len;
+    if (window > 0 && (int64_t)window + 63 < span) span = (int64_t)window + 63;
+    const int64_t n = (span + split_tokens - 1) / split_tokens;
+    return (int32_t)(n < 1 ? 1 : n);
+}
+
+size_t pz_decode_attn_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim,
+                                      int32_t n_splits) {
+    if (batch <= 0 || n_q_heads <= 0 || head_dim <= 0 || n_splits <= 0) return 0;
+    return (size_t)batch * (size_t)n_q_heads * (size_t)n_splits * (size_t)(head_dim + 2) * sizeof(float);
+}
+
+pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *block_table,
+                         int32_t max_pages_per_seq, const int32_t *seq_lens, int32_t batch,
+                         int32_t n_q_heads, const float *sinks, float sm_scale, float k_scale,
+                         float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits,
+                         void *workspace, size_t workspace_bytes, void *out, int32_t out_dtype,
+                         void *hip_stream) {
+    const pz_status cs = check_cache(cache);
+    if (cs != PZ_OK) return cs;
+    if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || split_tokens < 0)
+        return PZ_ERR_SHAPE;
+    if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
+    if (n_q_heads / cache->n_kv_heads > 8) return PZ_ERR_UNSUPPORTED;
+    if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
+    if (!positive_finite(sm_scale) || !positive_finite(k_scale) || !positive_finite(v_scale))
+        return PZ_ERR_SHAPE;
+    if (split_tokens % 64 != 0) return PZ_ERR_UNSUPPORTED;
+    if (batch == 0) return PZ_OK;
+    if (q == nullptr || block_table == nullptr || seq_lens == nullptr) return PZ_ERR_NULL;
+    if (split_tokens > 0) {
+        if (n_splits <= 0) return PZ_ERR_SHAPE;
+        if (workspace == nullptr) return PZ_ERR_WORKSPACE;
+        if (workspace_bytes < pz_decode_attn_workspace_bytes(batch, n_q_heads, cache->head_dim, n_splits))
+            return PZ_ERR_WORKSPACE;
+    } else if (out == nullptr) {
+        return PZ_ERR_NULL;
+    }
+    const int n_chunks = split_tokens > 0 ? n_splits : 1;
+    if ((int64_t)batch * cache->n_kv_heads * n_chunks > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+
+    pz::AttnParams p;
+    p.k = static_cast<const uint8_t *>(cache->k);
+    p.v = static_cast<const uint8_t *>(cache->v);
+    p.q = static_cast<const uint16_t *>(q);
+    p.block_table = block_table;
+    p.seq_lens = seq_lens;
+    p.sinks = sinks;
+    p.ws_acc = static_cast<float *>(workspace);
+    p.ws_ml = split_tokens > 0
+                  ? static_cast<float *>(workspace) + (size_t)batch * n_q_heads * n_splits * cache->head_dim
+                  : nullptr;
+    p.out = out;
+    p.max_pages = max_pages_per_seq;
+    p.B = batch;
+    p.Hq = n_q_heads;
+    p.Hkv = cache->n_kv_heads;
+    p.G = n_q_heads / cache->n_kv_heads;
+    p.window = window;
+    p.split_tokens = split_tokens;
+    p.n_splits = split_tokens > 0 ? n_splits : 1;
+    p.out_dtype = out_dtype;
+    p.sc = sm_scale * k_scale * 1.4426950408889634f;
+    p.v_scale = v_scale;
+
+    // upper bound of the 64-position steps one workgroup may see
+    int64_t max_tokens = (int64_t)max_pages_per_seq * cache->page_size;
+    if (window > 0 && (int64_t)window + 63 < max_tokens) max_tokens = (int64_t)window + 63;
+    if (split_tokens > 0 && split_tokens < max_tokens) max_tokens = split_tokens;
+    const int max_steps = (int)((max_tokens + 63) / 64);
+    const int n_waves = pick_waves(batch, cache->n_kv_heads, max_steps, n_chunks);
+    const hipError_t e = pz::launch_decode_attn(p, cache->page_size, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
+                                                n_waves, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
+pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_bytes, int32_t batch,
+                                       int32_t n_q_heads, int32_t head_dim, int32_t n_splits,
+                                       const int32_t *seq_lens, int32_t window, int32_t split_tokens,
+                                       const float *sinks, float v_scale, void *out, int32_t out_dtype,
+                                       void *hip_stream) {
+    if (batch < 0 || n_q_heads <= 0 || head_dim <= 0 || n_splits <= 0 || window < 0) return PZ_ERR_SHAPE;
+    if (head_dim != 64) return PZ_ERR_UNSUPPORTED;
+    if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
+    if (seq_lens != nullptr && (split_tokens <= 0 || split_tokens % 64 != 0)) return PZ_ERR_SHAPE;
+    if (!positive_finite(v_scale)) return PZ_ERR_SHAPE;
+    if (batch == 0) return PZ_OK;
+    if (workspace == nullptr) return PZ_ERR_WORKSPACE;
+    if (workspace_bytes < pz_decode_attn_workspace_bytes(batch, n_q_heads, head_dim, n_splits))
+        return PZ_ERR_WORKSPACE;
+    if (out == nullptr) return PZ_ERR_NULL;
+    if ((int64_t)batch * n_q_heads > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+    pz::ReduceParams p;
+    p.ws_acc = static_cast<const float *>(workspace);
+    p.ws_ml = static_cast<const float *>(workspace) + (size_t)batch * n_q_heads * n_splits * head_dim;
+    p.seq_lens = seq_lens;
+    p.sinks = sinks;
+    p.out = out;
+    p.B = batch;
+    p.Hq = n_q_heads;
+    p.n_splits = n_splits;
+    p.window = window;
+    p.split_tokens = split_tokens;
+    p.out_dtype = out_dtype;
+    p.v_scale = v_scale;
+    const hipError_t e = pz::launch_splitk_reduce(p, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// Quantise-and-append kernel for gfx950: new K/V rows (bf16) -> paged cache (E4M3 or bf16).
+//
+// Operation: code = e4m3(x / scale), round to nearest even, saturating at +-448 (paper
+// Section 3, "KV Quantization": FP8 KV cache with max-calibrated per-layer K and V scales).
+// The division is a correctly rounded fp32 division; the hardware convert
+// (v_cvt_pk_fp8_f32) rounds to nearest even but turns out-of-range inputs into NaN, so the
+// quotient is clamped to +-448 first (NaN inputs bypass the clamp and stay NaN).
+//
+// Work split: one workgroup = up to 64 tokens of one KV head.
+//   K ([page][head][P][64]): 4 threads per token, 16 channels each -> one 16-byte store; the 16
+//     tokens of a wave write 16 x 64 B rows (contiguous when their slots are).
+//   V ([page][head][64][P]): lane = token, each wave walks 16 channels -> byte stores that are
+//     contiguous across the lanes of a wave when the tokens' slots are contiguous.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pz_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+__device__ __forceinline__ float bf16_to_f32(unsigned bits16) { return __uint_as_float(bits16 << 16); }
+
+__device__ __forceinline__ float scaled_clamped(float x, float scale) {
+    const float r = __fdiv_rn(x, scale);
+    return (r != r) ? r : __builtin_amdgcn_fmed3f(r, -448.0f, 448.0f);
+}
+
+// two bf16 values packed in one dword -> two E4M3 codes in the low (hi=false) or high word of old
+__device__ __forceinline__ unsigned quant_pair(unsigned packed_bf16, float scale, unsigned old, bool hi) {
+    const float a = scaled_clamped(bf16_to_f32(packed_bf16 & 0xffffu), scale);
+    const float b = scaled_clamped(bf16_to_f32(packed_bf16 >> 16), scale);
+    return hi ? (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
+              : (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
+}
+
+__device__ __forceinline__ unsigned quant_one(unsigned bits16, float scale) {
+    const float a = scaled_clamped(bf16_to_f32(bits16), scale);
+    return (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, a, 0, false) & 0xffu;
+}
+
+template <int EB>
+__global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams prm) {
+    const int64_t t0 = (int64_t)blockIdx.x * 64;
+    const int g = blockIdx.y;
+    const int P = prm.P, Hkv = prm.Hkv;
+
+    {   // ---- K: thread = (token, 16-channel part)
+        const int64_t t = t0 + (threadIdx.x >> 2);
+        const int part = threadIdx.x & 3;
+        if (t < prm.T) {
+            const int64_t slot = prm.slot_mapping[t];
+            if (slot >= 0) {
+                const int64_t page = slot / P, off = slot % P;
+                const u32x4 *src = reinterpret_cast<const u32x4 *>(prm.k_new + (t * Hkv + g) * 64 + part * 16);
+                const u32x4 x0 = src[0], x1 = src[1];
+                uint8_t *dst = prm.k + (((page * Hkv + g) * P + off) * 64 + part * 16) * EB;
+                if constexpr (EB == 1) {
+                    u32x4 o;
+                    o[0] = quant_pair(x0[1], prm.k_scale, quant_pair(x0[0], prm.k_scale, 0u, false), true);
+                    o[1] = quant_pair(x0[3], prm.k_scale, quant_pair(x0[2], prm.k_scale, 0u, false), true);
+                    o[2] = quant_pair(x1[1], prm.k_scale, quant_pair(x1[0], prm.k_scale, 0u, false), true);
+                    o[3] = quant_pair(x1[3], prm.k_scale, quant_pair(x1[2], prm.k_scale, 0u, false), true);
+                    *reinterpret_cast<u32x4 *>(dst) = o;
+                } else {
+                    reinterpret_cast<u32x4 *>(dst)[0] = x0;
+                    reinterpret_cast<u32x4 *>(dst)[1] = x1;
+                }
+            }
+        }
+    }
+    {   // ---- V: lane = token, wave = 16-channel part
+        const int64_t t = t0 + (threadIdx.x & 63);
+        const int c0 = (threadIdx.x >> 6) * 16;
+        if (t < prm.T) {
+            const int64_t slot = prm.slot_mapping[t];
+            if (slot >= 0) {
+                const int64_t page = slot / P, off = slot % P;
+                const uint16_t *src = prm.v_new + (t * Hkv + g) * 64 + c0;
+                uint8_t *dst = prm.v + (((page * Hkv + g) * 64 + c0) * P + off) * EB;
+                const u32x4 x0 = reinterpret_cast<const u32x4 *>(src)[0];
+                const u32x4 x1 = reinterpret_cast<const u32x4 *>(src)[1];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const unsigned w = (i < 8) ? x0[i / 2] : x1[(i - 8) / 2];
+                    const unsigned bits = (i & 1) ? (w >> 16) : (w & 0xffffu);
+                    if constexpr (EB == 1) dst[(int64_t)i * P] = (uint8_t)quant_one(bits, prm.v_scale);
+                    else reinterpret_cast<uint16_t *>(dst)[(int64_t)i * P] = (uint16_t)bits;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+namespace pz {
+
+hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t stream) {
+    const dim3 grid((unsigned)((prm.T + 63) / 64), (unsigned)prm.Hkv), block(256);
+    if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_kernel<1>, grid, block, 0, stream, prm);
+    else hipLaunchKernelGGL(kv_append_kernel<2>, grid, block, 0, stream, prm);
+    return hipGetLastError();
+}
+
+}  // namespace pz

@@ -1,0 +1,453 @@
+// Decode attention over the paged FP8 / bf16 KV cache for gfx950 (MI355X): split-K partial or
+// single-pass kernel, and the log-sum-exp merge kernel.
+//
+// Operation: softmax attention of one query token per sequence against the cached K/V, grouped
+// query heads sharing a KV head, optional sliding window ("most recent W tokens", paper
+// Section 2, "Window attention for long-context inference"), cache stored as E4M3 codes with
+// per-layer K/V scales that multiply on dequantisation (paper Section 3, "KV Quantization").
+//
+// Mapping to the hardware (one wave64 = one independent stream over the KV of one KV head):
+//   * A "step" is 64 consecutive logical positions of one (sequence, KV head): 4 KiB of K and
+//     4 KiB of V in FP8.  Every lane fetches 4 + 4 aligned 16-byte pieces straight from HBM into
+//     registers; each wave-wide load instruction covers whole 256-byte (K) or 1-KiB (V) runs.
+//     There is no reuse between waves, so nothing is staged through LDS; the loads of step s+1
+//     are issued before step s is computed (register double buffering).
+//   * S^T = K Q^T on the matrix cores (v_mfma_f32_16x16x32_bf16): A = 16 cached positions x 32
+//     channels, B = Q^T with the group's (up to 8) query heads in columns 0..7 and again in
+//     columns 8..15.  E4M3 -> bf16 is exact (one v_cvt_scalef32_pk_bf16_fp8 per two codes), q is
+//     bf16, products are exact in fp32.
+//   * The result layout gives every lane 16 consecutive positions of one query-head column, so
+//     the online softmax needs cross-lane traffic only for the running maximum (lanes n, n+16,
+//     n+32, n+48).  exp is v_exp_f32 on log2-scaled logits.
+//   * O^T = V^T P^T on the matrix cores with V stored channel-major ([d][page_size]), so the A
+//     operand is again a direct 8-byte slice of what was loaded.  P is fed as bf16 in two
+//     terms: columns 0..7 carry the top 8 significant bits of p, columns 8..15 the next 8, which
+//     keeps p to ~2^-16 relative; the two halves are added at the end.  The softmax
+//     denominator is accumulated from the unsplit fp32 p.
+//   * Waves of a workgroup own disjoint step ranges and are merged through LDS (2 KiB per
+//     wave); the workgroup then writes either a sink-free partial (split-K) or the final row.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pz_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int kMaxWaves = 8;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ unsigned as_u32(bf16x2 v) { return __builtin_bit_cast(unsigned, v); }
+
+// two dwords holding 8 E4M3 codes -> 8 bf16 (exact)
+__device__ __forceinline__ bf16x8 dequant8(unsigned w0, unsigned w1) {
+    u32x4 r;
+    r[0] = as_u32(__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, false));
+    r[1] = as_u32(__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w0, 1.0f, true));
+    r[2] = as_u32(__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, false));
+    r[3] = as_u32(__builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w1, 1.0f, true));
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// upper halves of two fp32 -> packed bf16 pair (truncation), first value in the low half
+__device__ __forceinline__ unsigned pack_hi16(float first, float second) {
+    return __builtin_amdgcn_perm(__float_as_uint(second), __float_as_uint(first), 0x07060302u);
+}
+
+__device__ __forceinline__ float fmax3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+__device__ __forceinline__ float bf16_round_to_f32bits(float x, uint16_t *bits) {
+    unsigned u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) { *bits = (uint16_t)((u >> 16) | 0x40u); return x; }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    *bits = (uint16_t)(u >> 16);
+    return x;
+}
+
+__device__ __forceinline__ void store_out(void *out, int out_dtype, int64_t idx, float x) {
+    if (out_dtype == 0) {
+        reinterpret_cast<float *>(out)[idx] = x;
+    } else {
+        uint16_t b;
+        bf16_round_to_f32bits(x, &b);
+        reinterpret_cast<uint16_t *>(out)[idx] = b;
+    }
+}
+
+// One step's K and V pieces of a lane.  EB = bytes per cache element (1: E4M3, 2: bf16).
+template <int EB>
+struct Tile {
+    u32x4 k[4 * EB];
+    u32x4 v[4 * EB];
+};
+
+struct LaneGeom {
+    int kslot, vslot;        // which of the step's pages holds this lane's K rows / V columns
+    unsigned koff, voff;     // byte offset of the lane's first piece inside the page tile
+};
+
+template <int P, int EB>
+__device__ __forceinline__ LaneGeom lane_geom(int lane) {
+    const int t = lane & 15, kb = lane >> 4;
+    LaneGeom g;
+    const int krow0 = 16 * (t >> 2) + (t & 3);        // position (within the step) of K tile 0
+    g.kslot = krow0 / P;
+    g.koff = (unsigned)((krow0 % P) * 64 * EB + kb * 16 * EB);
+    const int vtok0 = 16 * kb;                         // first of the lane's 16 positions
+    g.vslot = vtok0 / P;
+    g.voff = (unsigned)(t * P * EB + (vtok0 % P) * EB);
+    return g;
+}
+
+template <int P, int EB>
+__device__ __forceinline__ void load_tile(Tile<EB> &tile, const uint8_t *__restrict__ kpage,
+                                          const uint8_t *__restrict__ vpage, const LaneGeom &g) {
+    // K: tile j holds rows 16*(t/4) + 4*j + (t%4): +4 rows per j
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < EB; ++e)
+            tile.k[j * EB + e] =
+                *reinterpret_cast<const u32x4 *>(kpage + g.koff + j * (4 * 64 * EB) + e * 16);
+    // V: channel tile c holds channels 16*c + t: +16 rows of P elements per c
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int e = 0; e < EB; ++e)
+            tile.v[c * EB + e] =
+                *reinterpret_cast<const u32x4 *>(vpage + g.voff + c * (16 * P * EB) + e * 16);
+}
+
+// MFMA A operand of K tile j, channel half i (channels 16*kb + 8*i .. +7)
+template <int EB>
+__device__ __forceinline__ bf16x8 k_operand(const Tile<EB> &tile, int j, int i) {
+    if constexpr (EB == 1) return dequant8(tile.k[j][2 * i], tile.k[j][2 * i + 1]);
+    else return __builtin_bit_cast(bf16x8, tile.k[2 * j + i]);
+}
+
+// MFMA A operand of V channel tile c, position half s2 (positions 16*kb + 8*s2 .. +7)
+template <int EB>
+__device__ __forceinline__ bf16x8 v_operand(const Tile<EB> &tile, int c, int s2) {
+    if constexpr (EB == 1) return dequant8(tile.v[c][2 * s2], tile.v[c][2 * s2 + 1]);
+    else return __builtin_bit_cast(bf16x8, tile.v[2 * c + s2]);
+}
+
+// zero the V elements of positions whose bit in `valid` (16 bits, bit i = lane position i) is 0
+template <int EB>
+__device__ __forceinline__ void mask_v(Tile<EB> &tile, unsigned valid) {
+#pragma unroll
+    for (int y = 0; y < 4 * EB; ++y) {           // dword y of the lane's 16 positions
+        unsigned m;
+        if constexpr (EB == 1) {
+            unsigned b = (valid >> (4 * y)) & 15u;
+            m = ((b & 1u) ? 0x000000ffu : 0u) | ((b & 2u) ? 0x0000ff00u : 0u) |
+                ((b & 4u) ? 0x00ff0000u : 0u) | ((b & 8u) ? 0xff000000u : 0u);
+        } else {
+            unsigned b = (valid >> (2 * y)) & 3u;
+            m = ((b & 1u) ? 0x0000ffffu : 0u) | ((b & 2u) ? 0xffff0000u : 0u);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tile.v[c * EB + y / 4][y % 4] &= m;
+    }
+}
+
+struct WaveState {
+    float m;          // running maximum of the log2-scaled logits of this lane's head column
+    float l;          // this lane's share of the denominator (its own 16 positions per step)
+    f32x4 o[4];       // O^T: channel 16*c + 4*kb + r of the lane's head column
+};
+
+// One 64-position step.  `valid`: 16-bit mask of the lane's positions (only read when MASKED).
+template <int EB, bool MASKED>
+__device__ __forceinline__ void compute_step(Tile<EB> &tile, const bf16x8 (&qb)[2], float sc,
+                                             unsigned lo_mask, unsigned valid, WaveState &st) {
+    // S^T tiles: sacc[j][r] = logit of position 16*kb + 4*j + r for head column n
+    f32x4 sacc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_operand<EB>(tile, j, 0), qb[0], z, 0, 0, 0);
+        sacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_operand<EB>(tile, j, 1), qb[1], z, 0, 0, 0);
+    }
+    if constexpr (MASKED) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
+        mask_v<EB>(tile, valid);
+    }
+    // maximum over the step's 64 positions of this head column
+    float mx = fmax3(sacc[0][0], sacc[0][1], sacc[0][2]);
+    mx = fmax3(mx, sacc[0][3], sacc[1][0]);
+    mx = fmax3(mx, sacc[1][1], sacc[1][2]);
+    mx = fmax3(mx, sacc[1][3], sacc[2][0]);
+    mx = fmax3(mx, sacc[2][1], sacc[2][2]);
+    mx = fmax3(mx, sacc[2][3], sacc[3][0]);
+    mx = fmax3(mx, sacc[3][1], sacc[3][2]);
+    mx = fmaxf(mx, sacc[3][3]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(st.m, mx * sc);          // sc > 0
+    // m_new is finite here: every processed step holds at least one valid position
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+    float p[16];
+    float psum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p[4 * j + r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j][r], sc, -m_new));
+            psum += p[4 * j + r];
+        }
+    st.l = st.l * alpha + psum;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) st.o[c] *= alpha;
+    }
+    // P^T operand: head columns 0..7 take the top bf16 of p, columns 8..15 the remainder
+    u32x4 pw[2];
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        float x0 = p[i] - __uint_as_float(__float_as_uint(p[i]) & lo_mask);
+        float x1 = p[i + 1] - __uint_as_float(__float_as_uint(p[i + 1]) & lo_mask);
+        pw[i / 8][(i % 8) / 2] = pack_hi16(x0, x1);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<EB>(tile, c, 0),
+                                                          __builtin_bit_cast(bf16x8, pw[0]), st.o[c], 0, 0, 0);
+        st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<EB>(tile, c, 1),
+                                                          __builtin_bit_cast(bf16x8, pw[1]), st.o[c], 0, 0, 0);
+    }
+}
+
+// 16-bit validity mask of a lane's positions [pos0, pos0 + 16) against [j0, j1)
+__device__ __forceinline__ unsigned valid_mask(int pos0, int j0, int j1) {
+    int a = min(max(j0 - pos0, 0), 16), b = min(max(j1 - pos0, 0), 16);
+    return ((1u << b) - 1u) & ~((1u << a) - 1u);
+}
+
+template <int P, int EB>
+__global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::AttnParams prm) {
+    constexpr int NPS = 64 / P;                        // pages per step
+    __shared__ float sm_acc[kMaxWaves][8][64];
+    __shared__ float sm_m[kMaxWaves][8];
+    __shared__ float sm_l[kMaxWaves][8];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = blockDim.x >> 6;
+    const int n_chunks = prm.split_tokens > 0 ? prm.n_splits : 1;
+    const int bg = blockIdx.x % (prm.B * prm.Hkv);     // chunk-major block order
+    const int chunk = blockIdx.x / (prm.B * prm.Hkv);
+    const int b = bg / prm.Hkv, g = bg % prm.Hkv;
+    const int G = prm.G;
+
+    const int L = prm.seq_lens[b];
+    const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
+    int j0 = lo, j1 = L;
+    if (prm.split_tokens > 0) {
+        const int a0 = lo & ~63;
+        j0 = max(lo, a0 + chunk * prm.split_tokens);
+        j1 = min(L, a0 + (chunk + 1) * prm.split_tokens);
+    }
+    const bool empty = j0 >= j1;                       // uniform over the workgroup
+
+    WaveState st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int n = lane & 15, kb = lane >> 4;
+    const int head = n & 7;
+
+    if (!empty) {
+        const int s_begin = j0 >> 6, s_end = (j1 + 63) >> 6;
+        const int n_steps = s_end - s_begin;
+        const int s0 = s_begin + (int)(((int64_t)n_steps * wave) / n_waves);
+        const int s1 = s_begin + (int)(((int64_t)n_steps * (wave + 1)) / n_waves);
+        if (s0 < s1) {
+            // Q^T operand: column n holds head n%8 of the group (zero beyond the group size)
+            bf16x8 qb[2];
+            {
+                u32x4 q0 = {0, 0, 0, 0}, q1 = {0, 0, 0, 0};
+                if (head < G) {
+                    const uint16_t *qrow = prm.q + ((int64_t)b * prm.Hq + g * G + head) * 64 + 16 * kb;
+                    q0 = *reinterpret_cast<const u32x4 *>(qrow);
+                    q1 = *reinterpret_cast<const u32x4 *>(qrow + 8);
+                }
+                qb[0] = __builtin_bit_cast(bf16x8, q0);
+                qb[1] = __builtin_bit_cast(bf16x8, q1);
+            }
+            const unsigned lo_mask = (n >= 8) ? 0xffff0000u : 0u;
+            const LaneGeom geom = lane_geom<P, EB>(lane);
+            const int64_t page_bytes = (int64_t)prm.Hkv * P * 64 * EB;
+            const uint8_t *kbase = prm.k + (int64_t)g * P * 64 * EB;
+            const uint8_t *vbase = prm.v + (int64_t)g * P * 64 * EB;
+            const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
+            const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
+
+            // lane i of `ids` holds the physical page of page index pbase + i (clamped)
+            int pbase = s0 * NPS;
+            int ids = bt[min(max(pbase + lane, pmin), pmax)];
+
+            auto issue = [&](Tile<EB> &tile, int s) {
+                if (s * NPS - pbase >= 64) {
+                    pbase = s * NPS;
+                    ids = bt[min(max(pbase + lane, pmin), pmax)];
+                }
+                if constexpr (NPS == 1) {
+                    const int pid = __builtin_amdgcn_readlane(ids, s - pbase);
+                    const int64_t off = (int64_t)pid * page_bytes;
+                    load_tile<P, EB>(tile, kbase + off, vbase + off, geom);
+                } else {
+                    const int kp = __shfl(ids, s * NPS + geom.kslot - pbase);
+                    const int vp = __shfl(ids, s * NPS + geom.vslot - pbase);
+                    load_tile<P, EB>(tile, kbase + (int64_t)kp * page_bytes,
+                                     vbase + (int64_t)vp * page_bytes, geom);
+                }
+            };
+            auto consume = [&](Tile<EB> &tile, int s) {
+                const int base = s << 6;
+                if (base >= j0 && base + 64 <= j1) {
+                    compute_step<EB, false>(tile, qb, prm.sc, lo_mask, 0xffffu, st);
+                } else {
+                    compute_step<EB, true>(tile, qb, prm.sc, lo_mask,
+                                           valid_mask(base + 16 * kb, j0, j1), st);
+                }
+            };
+
+            Tile<EB> ta, tb;
+            issue(ta, s0);
+            for (int s = s0; s < s1; s += 2) {
+                if (s + 1 < s1) issue(tb, s + 1);
+                consume(ta, s);
+                if (s + 1 < s1) {
+                    if (s + 2 < s1) issue(ta, s + 2);
+                    consume(tb, s + 1);
+                }
+            }
+        }
+    }
+
+    // per-wave result -> LDS: add the two P halves, sum the denominator over the four lane groups
+    float l = st.l;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float x = st.o[c][r];
+            x += __shfl_xor(x, 8);
+            if (n < 8) sm_acc[wave][n][16 * c + 4 * kb + r] = x;
+        }
+    if (lane < 8) {
+        sm_m[wave][lane] = st.m;
+        sm_l[wave][lane] = l;
+    }
+    __syncthreads();
+
+    // merge the waves; write the final row (single pass) or the sink-free partial (split-K)
+    const bool final_pass = prm.split_tokens == 0;
+    for (int idx = threadIdx.x; idx < G * 64; idx += blockDim.x) {
+        const int h = idx >> 6, c = idx & 63;
+        const int qh = g * G + h;
+        float M = -INFINITY;
+        for (int w = 0; w < n_waves; ++w) M = fmaxf(M, sm_m[w][h]);
+        float sink2 = -INFINITY;
+        if (final_pass && prm.sinks != nullptr) sink2 = prm.sinks[qh] * kLog2e;
+        M = fmaxf(M, sink2);
+        float num = 0.f, den = 0.f;
+        if (M != -INFINITY) {
+            den = (sink2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sink2 - M);
+            for (int w = 0; w < n_waves; ++w) {
+                const float mw = sm_m[w][h];
+                if (mw == -INFINITY) continue;
+                const float f = __builtin_amdgcn_exp2f(mw - M);
+                num = __builtin_fmaf(sm_acc[w][h][c], f, num);
+                den = __builtin_fmaf(sm_l[w][h], f, den);
+            }
+        }
+        if (final_pass) {
+            const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
+            store_out(prm.out, prm.out_dtype, ((int64_t)b * prm.Hq + qh) * 64 + c, r);
+        } else {
+            const int64_t row = ((int64_t)b * prm.Hq + qh) * prm.n_splits + chunk;
+            prm.ws_acc[row * 64 + c] = num;
+            if (c == 0) {
+                prm.ws_ml[row * 2] = M * kLn2;
+                prm.ws_ml[row * 2 + 1] = den;
+            }
+        }
+    }
+}
+
+// Merge kernel: one wave per (sequence, query head), lane = channel.
+__global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParams prm) {
+    const int row = blockIdx.x;                        // b * Hq + h
+    const int b = row / prm.Hq, h = row % prm.Hq;
+    const int c = threadIdx.x;
+    int n = prm.n_splits;
+    if (prm.seq_lens != nullptr) {
+        const int L = prm.seq_lens[b];
+        const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
+        const int span = L - (lo & ~63);
+        n = min(n, (span + prm.split_tokens - 1) / prm.split_tokens);
+    }
+    const float *acc = prm.ws_acc + (int64_t)row * prm.n_splits * 64;
+    const float *ml = prm.ws_ml + (int64_t)row * prm.n_splits * 2;
+    const float sink = prm.sinks != nullptr ? prm.sinks[h] : -INFINITY;
+    float M = sink;
+    for (int i = 0; i < n; ++i) M = fmaxf(M, ml[2 * i]);
+    float num = 0.f, den = 0.f;
+    if (M != -INFINITY) {
+        den = (sink == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((sink - M) * kLog2e);
+#pragma unroll 4
+        for (int i = 0; i < n; ++i) {
+            const float mi = ml[2 * i];
+            const float f = (mi == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mi - M) * kLog2e);
+            num = __builtin_fmaf(acc[(int64_t)i * 64 + c], f, num);
+            den = __builtin_fmaf(ml[2 * i + 1], f, den);
+        }
+    }
+    const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
+    store_out(prm.out, prm.out_dtype, (int64_t)row * 64 + c, r);
+}
+
+}  // namespace
+
+namespace pz {
+
+hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_bytes, int n_waves,
+                              hipStream_t stream) {
+    const int n_chunks = prm.split_tokens > 0 ? prm.n_splits : 1;
+    const dim3 grid((unsigned)(prm.B * prm.Hkv * n_chunks)), block(64 * n_waves);
+#define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((decode_attn_kernel<P, EB>), grid, block, 0, stream, prm)
+    if (elem_bytes == 1) {
+        if (page_size == 64) PZ_LAUNCH(64, 1);
+        else if (page_size == 32) PZ_LAUNCH(32, 1);
+        else PZ_LAUNCH(16, 1);
+    } else {
+        if (page_size == 64) PZ_LAUNCH(64, 2);
+        else if (page_size == 32) PZ_LAUNCH(32, 2);
+        else PZ_LAUNCH(16, 2);
+    }
+#undef PZ_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(prm.B * prm.Hq)), dim3(64), 0, stream, prm);
+    return hipGetLastError();
+}
+
+}  // namespace pz

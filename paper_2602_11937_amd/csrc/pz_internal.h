@@ -1,0 +1,53 @@
+// Internal launch interface between the C-ABI layer (pz_api.hip) and the kernels.
+#ifndef PZ_INTERNAL_H
+#define PZ_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pz {
+
+struct AttnParams {
+    const uint8_t *k;            // K cache  [page][Hkv][P][64]
+    const uint8_t *v;            // V cache  [page][Hkv][64][P]
+    const uint16_t *q;           // bf16 [B][Hq][64]
+    const int32_t *block_table;  // [B][max_pages]
+    const int32_t *seq_lens;     // [B]
+    const float *sinks;          // [Hq] or nullptr
+    float *ws_acc;               // split-K partials [B][Hq][S][64]
+    float *ws_ml;                // [B][Hq][S][2]
+    void *out;                   // [B][Hq][64]
+    int32_t max_pages, B, Hq, Hkv, G;
+    int32_t window, split_tokens, n_splits, out_dtype;
+    float sc;                    // sm_scale * k_scale * log2(e)
+    float v_scale;
+};
+
+struct ReduceParams {
+    const float *ws_acc;
+    const float *ws_ml;
+    const int32_t *seq_lens;     // or nullptr
+    const float *sinks;          // or nullptr
+    void *out;
+    int32_t B, Hq, n_splits, window, split_tokens, out_dtype;
+    float v_scale;
+};
+
+struct AppendParams {
+    uint8_t *k;                  // K cache
+    uint8_t *v;                  // V cache
+    const uint16_t *k_new;       // bf16 [T][Hkv][64]
+    const uint16_t *v_new;
+    const int64_t *slot_mapping; // [T]
+    int64_t T;
+    int32_t Hkv, P;
+    float k_scale, v_scale;
+};
+
+hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_bytes, int n_waves,
+                              hipStream_t stream);
+hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream);
+hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t stream);
+
+}  // namespace pz
+#endif

@@ -1,0 +1,106 @@
+"""The C-ABI library loads without a GPU, exports every symbol include/pz.h declares, and rejects
+bad arguments on the host before anything is enqueued (no compute calls here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2602_11937_amd as pz
+from paper_2602_11937_amd.binding import _CCache
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pz.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pz_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"pz_kv_append_fp8", "pz_decode_attn", "pz_decode_attn_splitk_reduce"} <= set(names)
+    lib = C.CDLL(pz.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_host_side_helpers():
+    assert pz.pz_decode_attn_n_splits(65536, 0, 1024) == 64
+    assert pz.pz_decode_attn_n_splits(65536, 8192, 1024) == 9       # window + 63 positions at most
+    assert pz.pz_decode_attn_n_splits(100, 8192, 1024) == 1
+    assert pz.pz_decode_attn_n_splits(0, 0, 64) == 1
+    assert pz.pz_decode_attn_n_splits(100, 0, 100) == 0             # not a multiple of 64
+    assert pz.pz_decode_attn_workspace_bytes(16, 64, 64, 64) == 16 * 64 * 64 * 66 * 4
+    assert pz.pz_decode_attn_workspace_bytes(0, 64, 64, 64) == 0
+    assert pz.pz_status_string(0) == "PZ_OK" and "WORKSPACE" in pz.pz_status_string(-4)
+
+
+def cache(**kw):
+    a = dict(k=0x1000, v=0x2000, num_pages=4, page_size=64, n_kv_heads=8, head_dim=64, dtype=0)
+    a.update(kw)
+    return _CCache(a["k"], a["v"], a["num_pages"], a["page_size"], a["n_kv_heads"], a["head_dim"], a["dtype"])
+
+
+def attn(c, **kw):
+    a = dict(q=0x10, block_table=0x20, max_pages=4, seq_lens=0x30, batch=2, n_q_heads=64, sinks=None,
+             sm_scale=0.125, k_scale=0.01, v_scale=0.01, window=0, split_tokens=0, n_splits=0, workspace=None,
+             workspace_bytes=0, out=0x40, out_dtype=0)
+    a.update(kw)
+    return pz.pz_decode_attn(c, a["q"], a["block_table"], a["max_pages"], a["seq_lens"], a["batch"],
+                             a["n_q_heads"], a["sinks"], a["sm_scale"], a["k_scale"], a["v_scale"], a["window"],
+                             a["split_tokens"], a["n_splits"], a["workspace"], a["workspace_bytes"], a["out"],
+                             a["out_dtype"], stream=0, check=False)
+
+
+def test_decode_attn_rejects_bad_arguments_before_any_launch():
+    NULL, SHAPE, UNSUP, WS = -1, -2, -3, -4
+    assert attn(None) == NULL
+    assert attn(cache(k=None)) == NULL
+    assert attn(cache(), q=None) == NULL and attn(cache(), seq_lens=None) == NULL
+    assert attn(cache(), out=None) == NULL
+    assert attn(cache(head_dim=128)) == UNSUP and attn(cache(page_size=48)) == UNSUP
+    assert attn(cache(dtype=7)) == UNSUP
+    assert attn(cache(), n_q_heads=60) == SHAPE                      # not a multiple of the KV heads
+    assert attn(cache(n_kv_heads=2), n_q_heads=64) == UNSUP          # group of 32
+    assert attn(cache(), batch=-1) == SHAPE and attn(cache(), window=-5) == SHAPE
+    assert attn(cache(), sm_scale=0.0) == SHAPE and attn(cache(), k_scale=-1.0) == SHAPE
+    assert attn(cache(), v_scale=float("nan")) == SHAPE
+    assert attn(cache(), split_tokens=100) == UNSUP
+    assert attn(cache(), split_tokens=128, n_splits=2) == WS
+    assert attn(cache(), split_tokens=128, n_splits=2, workspace=0x50, workspace_bytes=100) == WS
+    assert attn(cache(), split_tokens=128, n_splits=0, workspace=0x50, workspace_bytes=1 << 30) == SHAPE
+    assert attn(cache(), out_dtype=3) == UNSUP
+    assert attn(cache(), batch=0) == 0                               # nothing to do is not an error
+
+
+def test_append_and_reduce_reject_bad_arguments():
+    def app(c, **kw):
+        a = dict(k_new=0x10, v_new=0x20, slots=0x30, n=4, ks=0.01, vs=0.01)
+        a.update(kw)
+        return pz.pz_kv_append_fp8(c, a["k_new"], a["v_new"], a["slots"], a["n"], a["ks"], a["vs"], stream=0,
+                                   check=False)
+    assert app(None) == -1 and app(cache(v=None)) == -1 and app(cache(), k_new=None) == -1
+    assert app(cache(), slots=None) == -1
+    assert app(cache(), n=-1) == -2 and app(cache(), ks=0.0) == -2
+    assert app(cache(page_size=8)) == -3
+    assert app(cache(), n=0) == 0
+
+    def red(**kw):
+        a = dict(ws=0x10, wsb=1 << 30, batch=2, hq=64, d=64, S=4, seq_lens=None, window=0, split=0, sinks=None,
+                 vs=0.01, out=0x20, odt=0)
+        a.update(kw)
+        return pz.pz_decode_attn_splitk_reduce(a["ws"], a["wsb"], a["batch"], a["hq"], a["d"], a["S"],
+                                               a["seq_lens"], a["window"], a["split"], a["sinks"], a["vs"],
+                                               a["out"], a["odt"], stream=0, check=False)
+    assert red(ws=None) == -4 and red(wsb=10) == -4
+    assert red(out=None) == -1 and red(d=128) == -3 and red(S=0) == -2
+    assert red(seq_lens=0x30, split=0) == -2 and red(vs=0.0) == -2
+    assert red(batch=0) == 0
+
+
+def test_error_wrapper_raises():
+    with pytest.raises(pz.PzError) as e:
+        pz.pz_decode_attn(cache(head_dim=128), 1, 1, 1, 1, 1, 8, None, 1, 1, 1, 0, 0, 0, None, 0, 1, stream=0)
+    assert e.value.status == -3

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bars: cache bytes bit-exact; attention outputs max-abs error <= 2e-3 of the oracle output's RMS
+(fp32 oracle; the fp64 oracle is reported beside it)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_11937_amd as pz
+import workloads as wl
+from gpu_helpers import DEV, dev_bits, gpu_attn, gpu_cache, to_oracle_layout
+from helpers import oracle_cache, rel_err
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def oracle_attn(case, kc, vc, **kw):
+    a = dict(sinks=case.sinks, sm_scale=case.sm_scale, k_scale=case.k_scale, v_scale=case.v_scale,
+             window=case.window, nthreads=8)
+    a.update(kw)
+    seq_lens = a.pop("seq_lens", case.seq_lens)
+    q = a.pop("q", case.q)
+    return oracle.decode_attn(kc, vc, case.P, q, case.block_table, seq_lens, **a)
+
+
+# ------------------------------------------------------------------ append: bit-exact
+
+@pytest.mark.parametrize("P", [16, 32, 64])
+@pytest.mark.parametrize("scales", ["amax", "pow2", "unit"])
+def test_append_bytes_bit_exact(P, scales):
+    case = wl.make_case("a", B=3, Hq=8, Hkv=2, d=64, P=P, seq_lens=[100, 37, 129], seed=P,
+                        pow2_scales=scales == "pow2", unit_scales=scales == "unit", outlier_frac=0.05)
+    cache = gpu_cache(case)
+    gk, gv = to_oracle_layout(cache)
+    ok, ov = oracle_cache(case)
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov)      # includes untouched canary bytes
+
+
+def test_append_every_bf16_value_and_negative_slots():
+    Hkv, d, P = 2, 64, 16
+    T = 65536 // (Hkv * d)
+    bits = np.arange(65536, dtype=np.uint16).reshape(T, Hkv, d)
+    rng = np.random.default_rng(0)
+    slots = rng.permutation(T + 40)[:T].astype(np.int64)
+    slots[::7] = -1
+    num_pages = (T + 40 + P - 1) // P
+    for k_scale, v_scale in ((1.0, 0.0123), (4.8 / 448, 2.0 ** -7), (3.0, 0.37)):
+        cache = pz.PagedCache.allocate(num_pages, P, Hkv, d, pz.KV_FP8, DEV, fill=0xAA)
+        pz.pz_kv_append_fp8(cache, dev_bits(bits), dev_bits(bits[::-1].copy()), torch.from_numpy(slots).to(DEV),
+                            T, k_scale, v_scale)
+        torch.cuda.synchronize()
+        gk, gv = to_oracle_layout(cache)
+        ok, ov = oracle.new_cache(num_pages * P, Hkv, d)
+        oracle.kv_append(ok, ov, bits, bits[::-1].copy(), slots, k_scale, v_scale)
+        nan_k = (ok & 0x7F) == 0x7F
+        nan_v = (ov & 0x7F) == 0x7F
+        assert nan_k.sum() > 100                                   # NaN inputs stay NaN (payload-free check)
+        assert np.array_equal(gk[~nan_k], ok[~nan_k]) and np.all((gk[nan_k] & 0x7F) == 0x7F)
+        assert np.array_equal(gv[~nan_v], ov[~nan_v]) and np.all((gv[nan_v] & 0x7F) == 0x7F)
+
+
+def test_append_bf16_cache_copies_bits():
+    case = wl.make_case("b", B=2, Hq=8, Hkv=2, d=64, P=32, seq_lens=[70, 33], seed=1)
+    cache = gpu_cache(case, dtype=pz.KV_BF16)
+    gk, gv = to_oracle_layout(cache)
+    ok, ov = oracle_cache(case, oracle.KV_BF16)
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
+
+
+def test_append_single_decode_token_per_sequence():
+    """The decode-step shape: one new token per sequence lands in an already filled cache."""
+    case = wl.make_case("c", B=5, Hq=8, Hkv=2, d=64, P=64, seq_lens=[65, 64, 1, 200, 128], seed=2)
+    last = case.offsets[1:] - 1
+    prefix = np.setdiff1d(np.arange(len(case.slot_mapping)), last)
+    slots_prefix = case.slot_mapping.copy()
+    slots_prefix[last] = -1
+    cache = gpu_cache(case, slots=slots_prefix)
+    pz.pz_kv_append_fp8(cache, dev_bits(case.k[last]), dev_bits(case.v[last]),
+                        torch.from_numpy(case.slot_mapping[last]).to(DEV), len(last), case.k_scale, case.v_scale)
+    torch.cuda.synchronize()
+    gk, gv = to_oracle_layout(cache)
+    ok, ov = oracle_cache(case)
+    assert len(prefix) > 0 and np.array_equal(gk, ok) and np.array_equal(gv, ov)
+
+
+# ------------------------------------------------------------------ attention: <= 2e-3 of RMS
+
+CASES = {
+    "cfg1_tiny": dict(B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37], sm_scale=0.125, seed=0),
+    "g8_p64_ragged": dict(B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 64, 65, 777], seed=1),
+    "g1": dict(B=3, Hq=2, Hkv=2, d=64, P=16, seq_lens=[5, 64, 170], seed=2),
+    "g2_p32": dict(B=3, Hq=4, Hkv=2, d=64, P=32, seq_lens=[33, 300, 96], seed=3),
+    "g8_hkv8": dict(B=2, Hq=64, Hkv=8, d=64, P=64, seq_lens=[640, 2500], seed=4),
+    "window20": dict(B=3, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37, 19], window=20, seed=5),
+    "window128_p64": dict(B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 128, 129, 50], window=128, seed=6),
+    "window_unaligned": dict(B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 333, 4000], window=300, seed=7),
+    "no_sinks": dict(B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37], sinks=False, seed=8),
+    "outliers": dict(B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[900, 2100], outlier_frac=0.05, seed=9),
+    "pow2_scales": dict(B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[500, 70], pow2_scales=True, seed=10),
+    "unit_scales": dict(B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[500, 70], unit_scales=True, seed=11),
+    "len_one_and_zero": dict(B=4, Hq=8, Hkv=2, d=64, P=16, seq_lens=[1, 2, 17, 1], seed=12),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+@pytest.mark.parametrize("split_tokens", [0, 64, 256])
+def test_attention_matches_oracle(name, split_tokens):
+    case = wl.make_case(name, **CASES[name])
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    gk, gv = to_oracle_layout(cache)
+    assert np.array_equal(gk, kc) and np.array_equal(gv, vc)
+    want = oracle_attn(case, kc, vc)
+    got = gpu_attn(case, cache, split_tokens=split_tokens)
+    assert not np.any(np.isnan(got))
+    e32, e64 = rel_err(got, want), rel_err(got, oracle_attn(case, kc, vc, accum="f64"))
+    print("%s split=%d: err vs f32 oracle %.2e, vs f64 oracle %.2e" % (name, split_tokens, e32, e64))
+    assert e32 <= TOL and e64 <= TOL
+
+
+def test_zero_length_rows_and_garbage_beyond_the_context():
+    """L_b = 0 gives a zero row; NaN codes in cache slots outside [lo, L) never reach the output."""
+    case = wl.make_case("z", B=4, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37, 64, 9], seed=13)
+    cache = gpu_cache(case, fill=0x7F)                             # unwritten slots decode to NaN
+    kc, vc = oracle_cache(case)
+    lens = np.array([100, 0, 50, 9], dtype=np.int32)               # shorter than what was appended
+    for window, split in ((0, 0), (0, 64), (24, 0), (24, 64)):
+        want = oracle_attn(case, kc, vc, seq_lens=lens, window=window)
+        got = gpu_attn(case, cache, seq_lens=lens, window=window, split_tokens=split)
+        assert np.all(got[1] == 0) and not np.any(np.isnan(got))
+        assert rel_err(got, want) <= TOL
+    # positions before the window start hold NaN codes too
+    k2 = case.k.copy()
+    off = case.offsets
+    k2[off[0]:off[0] + 70] = 0x7FC0                                 # bf16 NaN -> E4M3 NaN
+    case2 = wl.Case(**{**case.__dict__, "k": k2, "v": k2})
+    cache2 = gpu_cache(case2, fill=0x7F)
+    kc2, vc2 = oracle_cache(case2)
+    want = oracle_attn(case2, kc2, vc2, window=24)
+    got = gpu_attn(case2, cache2, window=24)
+    assert not np.any(np.isnan(want)) and not np.any(np.isnan(got)) and rel_err(got, want) <= TOL
+
+
+def test_special_cases_on_gpu():
+    case = wl.make_case("s", B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[300, 64, 1], seed=14)
+    cache = gpu_cache(case)
+    full = gpu_attn(case, cache, window=0)
+    assert np.array_equal(gpu_attn(case, cache, window=300), full)          # window >= L is full attention
+    assert np.array_equal(gpu_attn(case, cache, window=100000), full)
+    a = gpu_attn(case, cache, sinks=None)
+    b = gpu_attn(case, cache, sinks=np.full(case.Hq, -np.inf, dtype=np.float32))
+    assert np.array_equal(a, b)                                             # sink = -inf is plain softmax
+    kc, vc = oracle_cache(case)
+    assert rel_err(a, oracle_attn(case, kc, vc, sinks=None)) <= TOL
+    assert np.array_equal(gpu_attn(case, cache, v_scale=case.v_scale * 2), full * 2)
+    big = gpu_attn(case, cache, sinks=np.full(case.Hq, 300.0, dtype=np.float32))
+    assert np.all(big == 0)
+    assert np.array_equal(gpu_attn(case, cache), full)                      # deterministic
+
+
+def test_bf16_output_is_one_rounding_of_the_fp32_result():
+    case = wl.make_case("o", B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[300, 70], seed=15)
+    cache = gpu_cache(case)
+    f32 = gpu_attn(case, cache)
+    for split in (0, 128):
+        b16 = gpu_attn(case, cache, split_tokens=split, out_dtype=pz.OUT_BF16)
+        want = torch.from_numpy(gpu_attn(case, cache, split_tokens=split)).to(torch.bfloat16).float().numpy()
+        assert np.array_equal(b16, want)
+    assert rel_err(gpu_attn(case, cache, out_dtype=pz.OUT_BF16), f32) < 8e-3
+
+
+def test_bf16_kv_cache_variant():
+    case = wl.make_case("k", B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[700, 64, 130], seed=16)
+    cache = gpu_cache(case, dtype=pz.KV_BF16)
+    kb, vb = oracle_cache(case, oracle.KV_BF16)
+    want = oracle_attn(case, kb, vb, k_scale=1.0, v_scale=1.0)
+    for split, window in ((0, 0), (128, 0), (0, 100), (64, 100)):
+        want = oracle_attn(case, kb, vb, k_scale=1.0, v_scale=1.0, window=window)
+        got = gpu_attn(case, cache, k_scale=1.0, v_scale=1.0, split_tokens=split, window=window)
+        assert rel_err(got, want) <= TOL
+    case16 = wl.make_case("k16", B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37], seed=17)
+    cache16 = gpu_cache(case16, dtype=pz.KV_BF16)
+    kb, vb = oracle_cache(case16, oracle.KV_BF16)
+    got = gpu_attn(case16, cache16, k_scale=1.0, v_scale=1.0)
+    assert rel_err(got, oracle_attn(case16, kb, vb, k_scale=1.0, v_scale=1.0)) <= TOL
+
+
+# ------------------------------------------------------------------ split-K pieces
+
+def test_partials_match_the_chunked_oracle():
+    """Workspace contents against the oracle's chunked definition: what is unique about a partial
+    is acc/l (the chunk's softmax average) and m + log l (its log-sum-exp); emptiness is exact."""
+    case = wl.make_case("p", B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 130, 64], window=0, seed=18)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    for window, split in ((0, 256), (0, 64), (200, 128)):
+        S = pz.pz_decode_attn_n_splits(1000, window, split)
+        _, acc, ml = gpu_attn(case, cache, window=window, split_tokens=split, return_ws=True)
+        oacc, oml = oracle.decode_attn_partials(kc, vc, case.P, case.q, case.block_table, case.seq_lens,
+                                                case.sm_scale, case.k_scale, window, split, S, accum="f64")
+        empty = np.isneginf(oml[..., 0])
+        assert np.array_equal(np.isneginf(ml[..., 0]), empty)
+        assert np.all(ml[..., 1][empty] == 0) and np.all(acc[empty] == 0)
+        ne = ~empty
+        lse_g = ml[..., 0][ne] + np.log(ml[..., 1][ne])
+        lse_o = oml[..., 0][ne].astype(np.float64) + np.log(oml[..., 1][ne].astype(np.float64))
+        assert np.max(np.abs(lse_g - lse_o)) < 1e-4
+        avg_g = acc[ne] / ml[..., 1][ne][:, None]
+        avg_o = oacc[ne] / oml[..., 1][ne][:, None]
+        assert rel_err(avg_g, avg_o) <= TOL
+
+
+def test_reduce_kernel_alone_against_oracle_reduce():
+    rng = np.random.default_rng(19)
+    B, Hq, S, d = 3, 16, 7, 64
+    acc = rng.standard_normal((B, Hq, S, d)).astype(np.float32)
+    ml = np.stack([rng.standard_normal((B, Hq, S)) * 20, rng.uniform(1, 900, (B, Hq, S))], -1).astype(np.float32)
+    ml[0, :, 3] = (-np.inf, 0)
+    acc[0, :, 3] = 0
+    ml[1] = (-np.inf, 0)                                            # a row with only empty partials
+    acc[1] = 0
+    sinks = rng.standard_normal(Hq).astype(np.float32)
+    ws = torch.from_numpy(np.concatenate([acc.ravel(), ml.ravel()])).to(DEV)
+    for sk in (sinks, None):
+        out = torch.full((B, Hq, d), float("nan"), device=DEV)
+        skd = None if sk is None else torch.from_numpy(sk).to(DEV)
+        pz.pz_decode_attn_splitk_reduce(ws, ws.numel() * 4, B, Hq, d, S, None, 0, 0, skd, 0.37, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        want = oracle.splitk_reduce(acc, ml, sk, 0.37)
+        assert np.all(got[1] == 0) and not np.any(np.isnan(got))
+        assert rel_err(got, want) < 1e-5
+
+
+def test_split_count_invariance():
+    case = wl.make_case("i", B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[4000, 1500], seed=20)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    want = oracle_attn(case, kc, vc, accum="f64")
+    outs = [gpu_attn(case, cache, split_tokens=s) for s in (0, 64, 576, 1024, 4096)]
+    for o in outs:
+        assert rel_err(o, want) <= TOL
+        assert rel_err(o, outs[0]) < 1e-4
+    more = gpu_attn(case, cache, split_tokens=1024, n_splits=9)     # surplus chunks are empty
+    assert rel_err(more, outs[3]) < 1e-6
