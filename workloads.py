@@ -185,3 +185,79 @@ def kv_tokens_read(seq_lens, window: int) -> int:
 def kv_bytes_per_token(Hkv: int = 8, d: int = 64, elem_bytes: int = 1) -> int:
     """K and V bytes of one cached token of one layer."""
     return 2 * Hkv * d * elem_bytes
+
+
+# ------------------------------------------------------------------ full-size inputs, generated on the device
+
+@dataclass
+class DeviceLayer:
+    """One layer's decode inputs resident on the GPU (torch tensors), plus host-side metadata.
+
+    k_ctx / v_ctx (bf16 [sum L][Hkv][d]) are kept only when `keep_context` was asked for; the
+    benchmark drops them after the cache has been built."""
+    B: int
+    Hq: int
+    Hkv: int
+    d: int
+    P: int
+    window: int
+    sm_scale: float
+    seq_lens: np.ndarray
+    k_scale: float
+    v_scale: float
+    num_pages: int
+    block_table_host: np.ndarray
+    slot_mapping_host: np.ndarray
+    q: object
+    sinks: object
+    block_table: object
+    seq_lens_dev: object
+    new_slots: object                     # int64 [B]: slot of each sequence's last (new) token
+    k_new: object                         # bf16 [B][Hkv][d]: the new token's K rows
+    v_new: object
+    k_ctx: object = None
+    v_ctx: object = None
+
+
+def device_layer(*, B, Hq=64, Hkv=8, d=64, P=64, seq_lens, window=0, seed=0, outlier_frac=0.0,
+                 outlier_gain=20.0, device="cuda"):
+    """Device-side twin of make_case for sizes that do not fit a host round trip comfortably.
+
+    Same recipe (N(0,1) -> bf16, sinks ~ N(0,1), outlier channels, amax/448 scales, random page
+    permutation), drawn from torch's seeded device generator instead of numpy's, so the values
+    differ from make_case's but the distribution and structure are the same.  The caller appends
+    k_ctx / v_ctx through the library and hands sampled sequences to the oracle."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    rng = np.random.default_rng(seed)
+    seq_lens = np.asarray(seq_lens, dtype=np.int32)
+    T = int(seq_lens.astype(np.int64).sum())
+    q = torch.randn((B, Hq, d), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+    sinks = torch.randn((Hq,), generator=g, device=device, dtype=torch.float32)
+    k = torch.empty((T, Hkv, d), dtype=torch.bfloat16, device=device)
+    v = torch.empty((T, Hkv, d), dtype=torch.bfloat16, device=device)
+    gain = torch.ones((Hkv * d,), dtype=torch.float32, device=device)
+    if outlier_frac > 0:
+        pairs = rng.choice(Hkv * d, size=int(round(outlier_frac * Hkv * d)), replace=False)
+        gain[torch.from_numpy(pairs).to(device)] = outlier_gain
+    gain = gain.view(1, Hkv, d)
+    step = 1 << 18
+    for t0 in range(0, T, step):
+        n = min(step, T - t0)
+        k[t0:t0 + n] = (torch.randn((n, Hkv, d), generator=g, device=device) * gain).to(torch.bfloat16)
+        v[t0:t0 + n] = torch.randn((n, Hkv, d), generator=g, device=device).to(torch.bfloat16)
+    k_amax = float(k.abs().max().float().item()) if T else 0.0
+    v_amax = float(v.abs().max().float().item()) if T else 0.0
+    k_scale = float(np.float32(k_amax) / np.float32(E4M3_MAX)) or 1.0
+    v_scale = float(np.float32(v_amax) / np.float32(E4M3_MAX)) or 1.0
+    num_pages, bt, slots = paged_tables(rng, seq_lens, P)
+    last = np.cumsum(seq_lens.astype(np.int64)) - 1
+    last_dev = torch.from_numpy(last).to(device)
+    return DeviceLayer(B=B, Hq=Hq, Hkv=Hkv, d=d, P=P, window=window, sm_scale=float(1.0 / np.sqrt(d)),
+                       seq_lens=seq_lens, k_scale=k_scale, v_scale=v_scale, num_pages=num_pages,
+                       block_table_host=bt, slot_mapping_host=slots, q=q, sinks=sinks,
+                       block_table=torch.from_numpy(bt).to(device),
+                       seq_lens_dev=torch.from_numpy(seq_lens).to(device),
+                       new_slots=torch.from_numpy(slots[last]).to(device),
+                       k_new=k[last_dev].contiguous(), v_new=v[last_dev].contiguous(), k_ctx=k, v_ctx=v)
