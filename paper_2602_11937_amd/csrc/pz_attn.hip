@@ -10,8 +10,9 @@
 //   * A "step" is 64 consecutive logical positions of one (sequence, KV head): 4 KiB of K and
 //     4 KiB of V in FP8.  Every lane fetches 4 + 4 aligned 16-byte pieces straight from HBM into
 //     registers; each wave-wide load instruction covers whole 256-byte (K) or 1-KiB (V) runs.
-//     There is no reuse between waves, so nothing is staged through LDS; the loads of step s+1
-//     are issued before step s is computed (register double buffering).
+//     There is no reuse between waves, so nothing is staged through LDS; the K registers are
+//     refilled with step s+1 as soon as QK^T of step s has consumed them, the V registers as
+//     soon as PV of step s has, so about one step's worth of loads is always in flight.
 //   * S^T = K Q^T on the matrix cores (v_mfma_f32_16x16x32_bf16): A = 16 cached positions x 32
 //     channels, B = Q^T with the group's (up to 8) query heads in columns 0..7 and again in
 //     columns 8..15.  E4M3 -> bf16 is exact (one v_cvt_scalef32_pk_bf16_fp8 per two codes), q is
@@ -79,10 +80,13 @@ __device__ __forceinline__ void store_out(void *out, int out_dtype, int64_t idx,
     }
 }
 
-// One step's K and V pieces of a lane.  EB = bytes per cache element (1: E4M3, 2: bf16).
+// One step's K pieces / V pieces of a lane.  EB = bytes per cache element (1: E4M3, 2: bf16).
 template <int EB>
-struct Tile {
+struct KTile {
     u32x4 k[4 * EB];
+};
+template <int EB>
+struct VTile {
     u32x4 v[4 * EB];
 };
 
@@ -104,42 +108,43 @@ __device__ __forceinline__ LaneGeom lane_geom(int lane) {
     return g;
 }
 
+// K: tile j holds rows 16*(t/4) + 4*j + (t%4) of the step: +4 rows per j
 template <int P, int EB>
-__device__ __forceinline__ void load_tile(Tile<EB> &tile, const uint8_t *__restrict__ kpage,
-                                          const uint8_t *__restrict__ vpage, const LaneGeom &g) {
-    // K: tile j holds rows 16*(t/4) + 4*j + (t%4): +4 rows per j
+__device__ __forceinline__ void load_k(KTile<EB> &tile, const uint8_t *__restrict__ kpage, unsigned koff) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int e = 0; e < EB; ++e)
-            tile.k[j * EB + e] =
-                *reinterpret_cast<const u32x4 *>(kpage + g.koff + j * (4 * 64 * EB) + e * 16);
-    // V: channel tile c holds channels 16*c + t: +16 rows of P elements per c
+            tile.k[j * EB + e] = *reinterpret_cast<const u32x4 *>(kpage + koff + j * (4 * 64 * EB) + e * 16);
+}
+
+// V: channel tile c holds channels 16*c + t: +16 rows of P elements per c
+template <int P, int EB>
+__device__ __forceinline__ void load_v(VTile<EB> &tile, const uint8_t *__restrict__ vpage, unsigned voff) {
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int e = 0; e < EB; ++e)
-            tile.v[c * EB + e] =
-                *reinterpret_cast<const u32x4 *>(vpage + g.voff + c * (16 * P * EB) + e * 16);
+            tile.v[c * EB + e] = *reinterpret_cast<const u32x4 *>(vpage + voff + c * (16 * P * EB) + e * 16);
 }
 
 // MFMA A operand of K tile j, channel half i (channels 16*kb + 8*i .. +7)
 template <int EB>
-__device__ __forceinline__ bf16x8 k_operand(const Tile<EB> &tile, int j, int i) {
+__device__ __forceinline__ bf16x8 k_operand(const KTile<EB> &tile, int j, int i) {
     if constexpr (EB == 1) return dequant8(tile.k[j][2 * i], tile.k[j][2 * i + 1]);
     else return __builtin_bit_cast(bf16x8, tile.k[2 * j + i]);
 }
 
 // MFMA A operand of V channel tile c, position half s2 (positions 16*kb + 8*s2 .. +7)
 template <int EB>
-__device__ __forceinline__ bf16x8 v_operand(const Tile<EB> &tile, int c, int s2) {
+__device__ __forceinline__ bf16x8 v_operand(const VTile<EB> &tile, int c, int s2) {
     if constexpr (EB == 1) return dequant8(tile.v[c][2 * s2], tile.v[c][2 * s2 + 1]);
     else return __builtin_bit_cast(bf16x8, tile.v[2 * c + s2]);
 }
 
 // zero the V elements of positions whose bit in `valid` (16 bits, bit i = lane position i) is 0
 template <int EB>
-__device__ __forceinline__ void mask_v(Tile<EB> &tile, unsigned valid) {
+__device__ __forceinline__ void mask_v(VTile<EB> &tile, unsigned valid) {
 #pragma unroll
     for (int y = 0; y < 4 * EB; ++y) {           // dword y of the lane's 16 positions
         unsigned m;
@@ -162,27 +167,20 @@ struct WaveState {
     f32x4 o[4];       // O^T: channel 16*c + 4*kb + r of the lane's head column
 };
 
-// One 64-position step.  `valid`: 16-bit mask of the lane's positions (only read when MASKED).
-template <int EB, bool MASKED>
-__device__ __forceinline__ void compute_step(Tile<EB> &tile, const bf16x8 (&qb)[2], float sc,
-                                             unsigned lo_mask, unsigned valid, WaveState &st) {
-    // S^T tiles: sacc[j][r] = logit of position 16*kb + 4*j + r for head column n
-    f32x4 sacc[4];
+// S^T tiles of one step: sacc[j][r] = raw dot product of position 16*kb + 4*j + r with head column n
+template <int EB>
+__device__ __forceinline__ void qk_step(const KTile<EB> &tile, const bf16x8 (&qb)[2], f32x4 (&sacc)[4]) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         f32x4 z = {0.f, 0.f, 0.f, 0.f};
         z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_operand<EB>(tile, j, 0), qb[0], z, 0, 0, 0);
         sacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_operand<EB>(tile, j, 1), qb[1], z, 0, 0, 0);
     }
-    if constexpr (MASKED) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
-        mask_v<EB>(tile, valid);
-    }
-    // maximum over the step's 64 positions of this head column
+}
+
+// Online softmax of one step for the lane's head column; returns the packed P^T operands.
+__device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigned lo_mask, WaveState &st,
+                                             u32x4 (&pw)[2]) {
     float mx = fmax3(sacc[0][0], sacc[0][1], sacc[0][2]);
     mx = fmax3(mx, sacc[0][3], sacc[1][0]);
     mx = fmax3(mx, sacc[1][1], sacc[1][2]);
@@ -212,13 +210,16 @@ __device__ __forceinline__ void compute_step(Tile<EB> &tile, const bf16x8 (&qb)[
         for (int c = 0; c < 4; ++c) st.o[c] *= alpha;
     }
     // P^T operand: head columns 0..7 take the top bf16 of p, columns 8..15 the remainder
-    u32x4 pw[2];
 #pragma unroll
     for (int i = 0; i < 16; i += 2) {
         float x0 = p[i] - __uint_as_float(__float_as_uint(p[i]) & lo_mask);
         float x1 = p[i + 1] - __uint_as_float(__float_as_uint(p[i + 1]) & lo_mask);
         pw[i / 8][(i % 8) / 2] = pack_hi16(x0, x1);
     }
+}
+
+template <int EB>
+__device__ __forceinline__ void pv_step(const VTile<EB> &tile, const u32x4 (&pw)[2], WaveState &st) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<EB>(tile, c, 0),
@@ -237,14 +238,16 @@ __device__ __forceinline__ unsigned valid_mask(int pos0, int j0, int j1) {
 template <int P, int EB>
 __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
-    __shared__ float sm_acc[kMaxWaves][8][64];
-    __shared__ float sm_m[kMaxWaves][8];
-    __shared__ float sm_l[kMaxWaves][8];
+    constexpr int GROUP = 64 / NPS;                    // steps whose page ids fit one register
+    // dynamic LDS, sized by the launch: per wave 8 heads x 64 channels, then 8 m's, then 8 l's
+    extern __shared__ float lds[];
+    float (*sm_acc)[8][64] = reinterpret_cast<float (*)[8][64]>(lds);
+    float (*sm_m)[8] = reinterpret_cast<float (*)[8]>(lds + (blockDim.x >> 6) * 512);
+    float (*sm_l)[8] = reinterpret_cast<float (*)[8]>(lds + (blockDim.x >> 6) * 520);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
-    const int n_chunks = prm.split_tokens > 0 ? prm.n_splits : 1;
     const int bg = blockIdx.x % (prm.B * prm.Hkv);     // chunk-major block order
     const int chunk = blockIdx.x / (prm.B * prm.Hkv);
     const int b = bg / prm.Hkv, g = bg % prm.Hkv;
@@ -294,46 +297,55 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             const uint8_t *vbase = prm.v + (int64_t)g * P * 64 * EB;
             const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
             const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
+            const float sc = prm.sc;
 
-            // lane i of `ids` holds the physical page of page index pbase + i (clamped)
-            int pbase = s0 * NPS;
-            int ids = bt[min(max(pbase + lane, pmin), pmax)];
-
-            auto issue = [&](Tile<EB> &tile, int s) {
-                if (s * NPS - pbase >= 64) {
-                    pbase = s * NPS;
-                    ids = bt[min(max(pbase + lane, pmin), pmax)];
-                }
-                if constexpr (NPS == 1) {
-                    const int pid = __builtin_amdgcn_readlane(ids, s - pbase);
-                    const int64_t off = (int64_t)pid * page_bytes;
-                    load_tile<P, EB>(tile, kbase + off, vbase + off, geom);
-                } else {
-                    const int kp = __shfl(ids, s * NPS + geom.kslot - pbase);
-                    const int vp = __shfl(ids, s * NPS + geom.vslot - pbase);
-                    load_tile<P, EB>(tile, kbase + (int64_t)kp * page_bytes,
-                                     vbase + (int64_t)vp * page_bytes, geom);
-                }
-            };
-            auto consume = [&](Tile<EB> &tile, int s) {
-                const int base = s << 6;
-                if (base >= j0 && base + 64 <= j1) {
-                    compute_step<EB, false>(tile, qb, prm.sc, lo_mask, 0xffffu, st);
-                } else {
-                    compute_step<EB, true>(tile, qb, prm.sc, lo_mask,
-                                           valid_mask(base + 16 * kb, j0, j1), st);
-                }
-            };
-
-            Tile<EB> ta, tb;
-            issue(ta, s0);
-            for (int s = s0; s < s1; s += 2) {
-                if (s + 1 < s1) issue(tb, s + 1);
-                consume(ta, s);
-                if (s + 1 < s1) {
-                    if (s + 2 < s1) issue(ta, s + 2);
-                    consume(tb, s + 1);
-                }
+            KTile<EB> kt;
+            VTile<EB> vt;
+            // The wave's steps are walked in groups whose page ids sit in one register (lane i
+            // holds the physical page of page index pbase + i, clamped to attended pages).  Inside
+            // a group the K buffer is refilled right after QK^T has consumed it and the V buffer
+            // right after PV, unconditionally; the group's last step is peeled so that no load
+            // is conditional and every wait counts exactly the loads issued after the one needed.
+            for (int gs = s0; gs < s1; gs += GROUP) {
+                const int ge = min(gs + GROUP, s1);
+                const int pbase = gs * NPS;
+                const int ids = bt[min(max(pbase + lane, pmin), pmax)];
+                auto k_page = [&](int s) -> const uint8_t * {
+                    int pid;
+                    if constexpr (NPS == 1) pid = __builtin_amdgcn_readlane(ids, s - gs);
+                    else pid = __shfl(ids, s * NPS + geom.kslot - pbase);
+                    return kbase + (int64_t)pid * page_bytes;
+                };
+                auto v_page = [&](int s) -> const uint8_t * {
+                    int pid;
+                    if constexpr (NPS == 1) pid = __builtin_amdgcn_readlane(ids, s - gs);
+                    else pid = __shfl(ids, s * NPS + geom.vslot - pbase);
+                    return vbase + (int64_t)pid * page_bytes;
+                };
+                auto step = [&](int s, bool prefetch) {
+                    const int base = s << 6;
+                    const bool full = base >= j0 && base + 64 <= j1;
+                    const unsigned valid = full ? 0xffffu : valid_mask(base + 16 * kb, j0, j1);
+                    f32x4 sacc[4];
+                    qk_step<EB>(kt, qb, sacc);
+                    if (prefetch) load_k<P, EB>(kt, k_page(s + 1), geom.koff);
+                    if (!full) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+                                sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
+                    }
+                    u32x4 pw[2];
+                    softmax_step(sacc, sc, lo_mask, st, pw);
+                    if (!full) mask_v<EB>(vt, valid);
+                    pv_step<EB>(vt, pw, st);
+                    if (prefetch) load_v<P, EB>(vt, v_page(s + 1), geom.voff);
+                };
+                load_k<P, EB>(kt, k_page(gs), geom.koff);
+                load_v<P, EB>(vt, v_page(gs), geom.voff);
+                for (int s = gs; s + 1 < ge; ++s) step(s, true);
+                step(ge - 1, false);
             }
         }
     }
@@ -431,7 +443,8 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
                               hipStream_t stream) {
     const int n_chunks = prm.split_tokens > 0 ? prm.n_splits : 1;
     const dim3 grid((unsigned)(prm.B * prm.Hkv * n_chunks)), block(64 * n_waves);
-#define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((decode_attn_kernel<P, EB>), grid, block, 0, stream, prm)
+    const size_t lds_bytes = (size_t)n_waves * (8 * 64 + 16) * sizeof(float);
+#define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((decode_attn_kernel<P, EB>), grid, block, lds_bytes, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);
         else if (page_size == 32) PZ_LAUNCH(32, 1);
