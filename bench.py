@@ -195,6 +195,7 @@ def main():
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
     ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-bf16", action="store_true", help="skip the BF16-KV comparison run")
+    ap.add_argument("--split-tokens", type=int, default=None, help="override the workload's split-K chunk length")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (the path needs no collective; see DESIGN.md on sharding): "
@@ -208,7 +209,10 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     pz.lib()                                                      # fails loudly if libpz.so is not built
-    spec = WORKLOADS[args.workload]
+    spec = dict(WORKLOADS[args.workload])
+    if args.split_tokens is not None:
+        spec["split_tokens"] = args.split_tokens
+        spec["text"] += " [split_tokens overridden to %d]" % args.split_tokens
     torch.cuda.set_device(0)
 
     t_setup = time.perf_counter()

@@ -33,15 +33,26 @@ int round_down_pow2(int x) {
     return r;
 }
 
-// waves per workgroup: the steps of one (sequence, KV head[, chunk]) are dealt to the waves
-int pick_waves(int batch, int n_kv_heads, int max_steps, int n_chunks) {
-    const int forced = env_int("PZ_ATTN_WAVES", 0);
-    if (forced > 0) return forced > 8 ? 8 : round_down_pow2(forced);
-    const long groups = (long)batch * n_kv_heads * n_chunks;
+// Launch shape.  The chip holds 1024 SIMDs; a wave streams best when it owns a long run of steps
+// (its start-up and its final store are latency it cannot hide), so:
+//   - with plenty of chunks, one-wave workgroups each walk several consecutive chunks
+//     (chunks_per_group), aiming at about 2 waves per SIMD;
+//   - with few (sequence, KV head, chunk) items, the steps of one item are dealt to several waves.
+void pick_shape(int batch, int n_kv_heads, int max_steps, int n_chunks, int *n_waves, int *chunks_per_group) {
+    const long items = (long)batch * n_kv_heads * n_chunks;
+    const int forced_w = env_int("PZ_ATTN_WAVES", 0);
+    const int forced_c = env_int("PZ_ATTN_CHUNKS_PER_GROUP", 0);
     int w = 1;
-    // aim at >= 4096 waves in flight (256 CUs x 4 SIMDs x 4) while keeping >= 2 steps per wave
-    while (w < 8 && groups * w < 4096 && max_steps >= 4 * w) w *= 2;
-    return w;
+    if (forced_w > 0) w = forced_w > 8 ? 8 : round_down_pow2(forced_w);
+    else while (w < 8 && items * w < 2048 && max_steps >= 4 * w) w *= 2;
+    int c = 1;
+    if (w == 1 && n_chunks > 1) {
+        if (forced_c > 0) c = forced_c;
+        else while (c < 8 && c < n_chunks && items / (2 * c) >= 2048) c *= 2;
+        if (c > n_chunks) c = n_chunks;
+    }
+    *n_waves = w;
+    *chunks_per_group = c;
 }
 
 }  // namespace
@@ -159,7 +170,9 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     if (window > 0 && (int64_t)window + 63 < max_tokens) max_tokens = (int64_t)window + 63;
     if (split_tokens > 0 && split_tokens < max_tokens) max_tokens = split_tokens;
     const int max_steps = (int)((max_tokens + 63) / 64);
-    const int n_waves = pick_waves(batch, cache->n_kv_heads, max_steps, n_chunks);
+    int n_waves = 1, chunks_per_group = 1;
+    pick_shape(batch, cache->n_kv_heads, max_steps, n_chunks, &n_waves, &chunks_per_group);
+    p.chunks_per_group = chunks_per_group;
     const hipError_t e = pz::launch_decode_attn(p, cache->page_size, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
                                                 n_waves, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;

@@ -235,11 +235,23 @@ __device__ __forceinline__ unsigned valid_mask(int pos0, int j0, int j1) {
     return ((1u << b) - 1u) & ~((1u << a) - 1u);
 }
 
+// x + (x of the lane 8 places away inside its row of 16 lanes), one DPP move
+__device__ __forceinline__ float add_ror8(float x) {
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x128, 0xf, 0xf, true));
+}
+
+// Grid: one workgroup per (sequence, KV head, chunk group).  Two modes:
+//   n_waves == 1 ("direct"): the wave walks every chunk of its group back to back -- the load
+//     pipeline is not drained at chunk boundaries -- and writes each chunk's partial (split-K)
+//     or the final row (single pass) straight from registers.
+//   n_waves  > 1: one chunk (or the whole sequence) per workgroup, its steps dealt to the waves,
+//     merged through LDS.
 template <int P, int EB>
 __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
     constexpr int GROUP = 64 / NPS;                    // steps whose page ids fit one register
-    // dynamic LDS, sized by the launch: per wave 8 heads x 64 channels, then 8 m's, then 8 l's
+    // dynamic LDS in records of 528 floats (8 heads x 64 channels, then 8 m's, then 8 l's):
+    // one record per wave (n_waves > 1), or one per chunk of the group (one-wave split-K)
     extern __shared__ float lds[];
     float (*sm_acc)[8][64] = reinterpret_cast<float (*)[8][64]>(lds);
     float (*sm_m)[8] = reinterpret_cast<float (*)[8]>(lds + (blockDim.x >> 6) * 512);
@@ -248,29 +260,79 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = blockDim.x >> 6;
-    const int bg = blockIdx.x % (prm.B * prm.Hkv);     // chunk-major block order
-    const int chunk = blockIdx.x / (prm.B * prm.Hkv);
+    const bool direct = n_waves == 1;
+    const bool final_pass = prm.split_tokens == 0;
+    const int bg = blockIdx.x % (prm.B * prm.Hkv);     // group-major block order
+    const int cgrp = blockIdx.x / (prm.B * prm.Hkv);
     const int b = bg / prm.Hkv, g = bg % prm.Hkv;
     const int G = prm.G;
+    const int n = lane & 15, kb = lane >> 4;
+    const int head = n & 7;
+    const int qh = g * G + head;                       // only meaningful when head < G
 
     const int L = prm.seq_lens[b];
     const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
+    const int a0 = lo & ~63;
+    const int c_first = cgrp * prm.chunks_per_group;   // first chunk of this workgroup
+    const int c_last = final_pass ? 1 : min(c_first + prm.chunks_per_group, prm.n_splits);
     int j0 = lo, j1 = L;
-    if (prm.split_tokens > 0) {
-        const int a0 = lo & ~63;
-        j0 = max(lo, a0 + chunk * prm.split_tokens);
-        j1 = min(L, a0 + (chunk + 1) * prm.split_tokens);
+    if (!final_pass) {
+        j0 = max(lo, a0 + c_first * prm.split_tokens);
+        j1 = (int)min((int64_t)L, (int64_t)a0 + (int64_t)c_last * prm.split_tokens);
     }
     const bool empty = j0 >= j1;                       // uniform over the workgroup
 
     WaveState st;
-    st.m = -INFINITY;
-    st.l = 0.f;
+    auto reset_state = [&]() {
+        st.m = -INFINITY;
+        st.l = 0.f;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < 4; ++c) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    reset_state();
 
-    const int n = lane & 15, kb = lane >> 4;
-    const int head = n & 7;
+    // direct mode: park the state as partial number `slot` of this wave in LDS (split-K; the
+    // partials go to HBM in one burst when the wave is done, so that no store sits between the
+    // loads of the pipeline), or write it as the final row (single pass); then reset it
+    auto emit_direct = [&](int slot) {
+        float l = st.l;
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        float scale = 1.0f;
+        if (final_pass) {
+            const float sink2 = (prm.sinks != nullptr && head < G) ? prm.sinks[qh] * kLog2e : -INFINITY;
+            const float M = fmaxf(st.m, sink2);
+            const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
+            const float den = l * f + ((sink2 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sink2 - M));
+            scale = (den > 0.f) ? prm.v_scale * f / den : 0.f;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            f32x4 x;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = add_ror8(st.o[c][r]) * scale;
+            if (n < 8 && head < G) {
+                if (final_pass) {
+                    const int64_t at = ((int64_t)b * prm.Hq + qh) * 64 + 16 * c + 4 * kb;
+                    if (prm.out_dtype == 0) {
+                        *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(prm.out) + at) = x;
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) store_out(prm.out, 1, at + r, x[r]);
+                    }
+                } else {
+                    *reinterpret_cast<f32x4 *>(&lds[slot * 528 + n * 64 + 16 * c + 4 * kb]) = x;
+                }
+            }
+        }
+        if (!final_pass && lane < 8) {
+            lds[slot * 528 + 512 + lane] = st.m * kLn2;
+            lds[slot * 528 + 520 + lane] = l;
+        }
+        reset_state();
+    };
+
+    int next_chunk = c_first;                          // direct split-K: first chunk not yet written
 
     if (!empty) {
         const int s_begin = j0 >> 6, s_end = (j1 + 63) >> 6;
@@ -283,7 +345,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             {
                 u32x4 q0 = {0, 0, 0, 0}, q1 = {0, 0, 0, 0};
                 if (head < G) {
-                    const uint16_t *qrow = prm.q + ((int64_t)b * prm.Hq + g * G + head) * 64 + 16 * kb;
+                    const uint16_t *qrow = prm.q + ((int64_t)b * prm.Hq + qh) * 64 + 16 * kb;
                     q0 = *reinterpret_cast<const u32x4 *>(qrow);
                     q1 = *reinterpret_cast<const u32x4 *>(qrow + 8);
                 }
@@ -298,6 +360,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
             const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
             const float sc = prm.sc;
+            const int steps_per_chunk = prm.split_tokens >> 6;
+            const int a0_step = a0 >> 6;
 
             KTile<EB> kt;
             VTile<EB> vt;
@@ -341,6 +405,12 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                     if (!full) mask_v<EB>(vt, valid);
                     pv_step<EB>(vt, pw, st);
                     if (prefetch) load_v<P, EB>(vt, v_page(s + 1), geom.voff);
+                    // direct split-K: a chunk ends after this step -> write its partial
+                    if (direct && !final_pass &&
+                        ((s + 1 - a0_step) % steps_per_chunk == 0 || s + 1 == s1)) {
+                        emit_direct(next_chunk - c_first);
+                        ++next_chunk;
+                    }
                 };
                 load_k<P, EB>(kt, k_page(gs), geom.koff);
                 load_v<P, EB>(vt, v_page(gs), geom.voff);
@@ -350,7 +420,31 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         }
     }
 
-    // per-wave result -> LDS: add the two P halves, sum the denominator over the four lane groups
+    if (direct) {
+        if (final_pass) {
+            emit_direct(0);
+            return;
+        }
+        // burst the parked partials out: one 256-byte row per head and chunk, lane = channel;
+        // chunks of the group that lie beyond the context are written as empty partials
+        __syncthreads();                               // lanes read what other lanes parked
+        for (int c = c_first; c < c_last; ++c) {
+            const bool parked = c < next_chunk;
+            const float *src = &lds[(c - c_first) * 528];
+            for (int h = 0; h < G; ++h) {
+                const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c;
+                prm.ws_acc[row * 64 + lane] = parked ? src[h * 64 + lane] : 0.f;
+                if (lane < 2) {
+                    const float empty_ml = lane == 0 ? -INFINITY : 0.f;
+                    prm.ws_ml[row * 2 + lane] = parked ? src[512 + 8 * lane + h] : empty_ml;
+                }
+            }
+        }
+        return;
+    }
+
+    // n_waves > 1: per-wave result -> LDS (add the two P halves, sum the denominator over the
+    // four lane groups), then merge and write the final row or the sink-free partial
     float l = st.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
@@ -358,8 +452,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float x = st.o[c][r];
-            x += __shfl_xor(x, 8);
+            const float x = add_ror8(st.o[c][r]);
             if (n < 8) sm_acc[wave][n][16 * c + 4 * kb + r] = x;
         }
     if (lane < 8) {
@@ -368,15 +461,13 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     }
     __syncthreads();
 
-    // merge the waves; write the final row (single pass) or the sink-free partial (split-K)
-    const bool final_pass = prm.split_tokens == 0;
     for (int idx = threadIdx.x; idx < G * 64; idx += blockDim.x) {
         const int h = idx >> 6, c = idx & 63;
-        const int qh = g * G + h;
+        const int qhead = g * G + h;
         float M = -INFINITY;
         for (int w = 0; w < n_waves; ++w) M = fmaxf(M, sm_m[w][h]);
         float sink2 = -INFINITY;
-        if (final_pass && prm.sinks != nullptr) sink2 = prm.sinks[qh] * kLog2e;
+        if (final_pass && prm.sinks != nullptr) sink2 = prm.sinks[qhead] * kLog2e;
         M = fmaxf(M, sink2);
         float num = 0.f, den = 0.f;
         if (M != -INFINITY) {
@@ -391,9 +482,9 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         }
         if (final_pass) {
             const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
-            store_out(prm.out, prm.out_dtype, ((int64_t)b * prm.Hq + qh) * 64 + c, r);
+            store_out(prm.out, prm.out_dtype, ((int64_t)b * prm.Hq + qhead) * 64 + c, r);
         } else {
-            const int64_t row = ((int64_t)b * prm.Hq + qh) * prm.n_splits + chunk;
+            const int64_t row = ((int64_t)b * prm.Hq + qhead) * prm.n_splits + c_first;
             prm.ws_acc[row * 64 + c] = num;
             if (c == 0) {
                 prm.ws_ml[row * 2] = M * kLn2;
@@ -403,11 +494,25 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     }
 }
 
-// Merge kernel: one wave per (sequence, query head), lane = channel.
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x = fmaxf(x, __shfl_xor(x, d));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d);
+    return x;
+}
+
+// Merge kernel: one wave per (sequence, query head).  The chunks are taken 64 at a time: lane i
+// fetches (m_i, l_i) of chunk i and computes its weight exp(m_i - M); then lane = channel and the
+// 64 accumulator rows are streamed with 16 independent loads in flight per lane, each scaled by
+// its chunk's weight read out of the weight register (uniform lane index).
 __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
-    const int c = threadIdx.x;
+    const int lane = threadIdx.x;
     int n = prm.n_splits;
     if (prm.seq_lens != nullptr) {
         const int L = prm.seq_lens[b];
@@ -416,23 +521,36 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParam
         n = min(n, (span + prm.split_tokens - 1) / prm.split_tokens);
     }
     const float *acc = prm.ws_acc + (int64_t)row * prm.n_splits * 64;
-    const float *ml = prm.ws_ml + (int64_t)row * prm.n_splits * 2;
+    const float2 *ml = reinterpret_cast<const float2 *>(prm.ws_ml) + (int64_t)row * prm.n_splits;
     const float sink = prm.sinks != nullptr ? prm.sinks[h] : -INFINITY;
-    float M = sink;
-    for (int i = 0; i < n; ++i) M = fmaxf(M, ml[2 * i]);
-    float num = 0.f, den = 0.f;
-    if (M != -INFINITY) {
-        den = (sink == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((sink - M) * kLog2e);
-#pragma unroll 4
-        for (int i = 0; i < n; ++i) {
-            const float mi = ml[2 * i];
-            const float f = (mi == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mi - M) * kLog2e);
-            num = __builtin_fmaf(acc[(int64_t)i * 64 + c], f, num);
-            den = __builtin_fmaf(ml[2 * i + 1], f, den);
+    float M = sink;                                    // running reference maximum
+    float num = 0.f;
+    float den = (sink == -INFINITY) ? 0.f : 1.0f;      // exp(sink - M) with M == sink
+    for (int base = 0; base < n; base += 64) {
+        const int cnt = min(64, n - base);
+        float2 v = {-INFINITY, 0.f};
+        if (lane < cnt) v = ml[base + lane];
+        const float M_new = fmaxf(M, wave_max(v.x));
+        if (M_new == -INFINITY) continue;              // only empty partials so far, no sink
+        const float keep = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((M - M_new) * kLog2e);
+        const float w = (v.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((v.x - M_new) * kLog2e);
+        num *= keep;
+        den = den * keep + wave_sum(v.y * w);
+        M = M_new;
+        const float *a = acc + (int64_t)base * 64 + lane;
+        for (int k = 0; k < cnt; k += 16) {
+            float x[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) x[u] = a[(int64_t)min(k + u, cnt - 1) * 64];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), min(k + u, 63)));
+                num = __builtin_fmaf(x[u], (k + u < cnt) ? wu : 0.f, num);
+            }
         }
     }
     const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
-    store_out(prm.out, prm.out_dtype, (int64_t)row * 64 + c, r);
+    store_out(prm.out, prm.out_dtype, (int64_t)row * 64 + lane, r);
 }
 
 }  // namespace
@@ -442,8 +560,10 @@ namespace pz {
 hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_bytes, int n_waves,
                               hipStream_t stream) {
     const int n_chunks = prm.split_tokens > 0 ? prm.n_splits : 1;
-    const dim3 grid((unsigned)(prm.B * prm.Hkv * n_chunks)), block(64 * n_waves);
-    const size_t lds_bytes = (size_t)n_waves * (8 * 64 + 16) * sizeof(float);
+    const int n_groups = (n_chunks + prm.chunks_per_group - 1) / prm.chunks_per_group;
+    const dim3 grid((unsigned)(prm.B * prm.Hkv * n_groups)), block(64 * n_waves);
+    const size_t records = n_waves > 1 ? n_waves : (prm.split_tokens > 0 ? prm.chunks_per_group : 0);
+    const size_t lds_bytes = records * (8 * 64 + 16) * sizeof(float);
 #define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((decode_attn_kernel<P, EB>), grid, block, lds_bytes, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);

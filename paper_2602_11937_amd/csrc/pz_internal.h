@@ -19,6 +19,7 @@ struct AttnParams {
     void *out;                   // [B][Hq][64]
     int32_t max_pages, B, Hq, Hkv, G;
     int32_t window, split_tokens, n_splits, out_dtype;
+    int32_t chunks_per_group;    // consecutive split-K chunks walked by one workgroup (1 unless it is one wave)
     float sc;                    // sm_scale * k_scale * log2(e)
     float v_scale;
 };

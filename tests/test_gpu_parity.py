@@ -245,3 +245,28 @@ def test_split_count_invariance():
         assert rel_err(o, outs[0]) < 1e-4
     more = gpu_attn(case, cache, split_tokens=1024, n_splits=9)     # surplus chunks are empty
     assert rel_err(more, outs[3]) < 1e-6
+
+
+# ------------------------------------------------------------------ launch shapes
+
+@pytest.mark.parametrize("waves,cpg", [(1, 1), (1, 2), (1, 3), (1, 8), (2, 1), (4, 1), (8, 1)])
+def test_every_launch_shape_gives_the_same_answer(waves, cpg, monkeypatch):
+    """Waves per workgroup and chunks per workgroup are launch heuristics; force each shape."""
+    monkeypatch.setenv("PZ_ATTN_WAVES", str(waves))
+    monkeypatch.setenv("PZ_ATTN_CHUNKS_PER_GROUP", str(cpg))
+    case = wl.make_case("l", B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[2000, 130, 700], seed=21)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    for window in (0, 300):
+        want = oracle_attn(case, kc, vc, window=window, accum="f64")
+        for split in (0, 128, 320):
+            got = gpu_attn(case, cache, window=window, split_tokens=split)
+            assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL, (window, split)
+        # surplus chunks (beyond every context) must come out as empty partials
+        _, acc, ml = gpu_attn(case, cache, window=window, split_tokens=128, n_splits=19, return_ws=True)
+        span = np.where(window > 0, np.minimum(case.seq_lens, window + 63), case.seq_lens)
+        for b in range(case.B):
+            lo = max(0, int(case.seq_lens[b]) - window) if window else 0
+            n_b = -(-(int(case.seq_lens[b]) - (lo - lo % 64)) // 128)
+            assert np.all(np.isneginf(ml[b, :, n_b:, 0])) and np.all(ml[b, :, n_b:, 1] == 0)
+            assert np.all(acc[b, :, n_b:] == 0) and np.all(np.isfinite(ml[b, :, :n_b, 0]))
