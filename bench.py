@@ -78,11 +78,17 @@ class Layer:
         if not keep_context:
             lay.k_ctx = lay.v_ctx = None
         del slots
-        self.S = pz.pz_decode_attn_n_splits(int(seq_lens.max()), self.window, self.split) if self.split else 0
-        self.ws_bytes = pz.pz_decode_attn_workspace_bytes(B, lay.Hq, lay.d, self.S) if self.split else 0
-        self.ws = torch.empty((max(self.ws_bytes, 4) // 4,), dtype=torch.float32, device="cuda")
         self.out = torch.empty((B, lay.Hq, lay.d), dtype=torch.float32, device="cuda")
         self.max_pages = int(lay.block_table_host.shape[1])
+        self.set_split(self.split)
+
+    def set_split(self, split_tokens):
+        """(Re)size the split-K workspace for a chunk length (0 = single pass)."""
+        pz, lay = self.pz, self.lay
+        self.split = split_tokens
+        self.S = pz.pz_decode_attn_n_splits(int(lay.seq_lens.max()), self.window, self.split) if self.split else 0
+        self.ws_bytes = pz.pz_decode_attn_workspace_bytes(lay.B, lay.Hq, lay.d, self.S) if self.split else 0
+        self.ws = self.torch.empty((max(self.ws_bytes, 4) // 4,), dtype=self.torch.float32, device="cuda")
 
     # algorithmic bytes: what the method must move (split-K workspace traffic is overhead)
     def attn_bytes(self, wl):
@@ -129,19 +135,21 @@ class Layer:
         self.reduce()
 
 
-def time_steps(torch, layers, steps, warmup):
-    """W untimed steps, then exactly K timed steps between synchronisations; the dominant
-    kernel (decode attention) is also bracketed by events on the launch stream in every step."""
+def time_steps(torch, layers, steps, warmup, events):
+    """W untimed steps, then exactly K timed steps between synchronisations.  With events=True the
+    dominant kernel (decode attention) is bracketed by events on the launch stream in every timed
+    step; the two event records cost about 5 us per step, so the step time that is reported as
+    `value` comes from a pass without them."""
     for i in range(warmup):
         layers[i % len(layers)].step()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        layers[(warmup + i) % len(layers)].step(evs[i])
+        layers[(warmup + i) % len(layers)].step(evs[i] if events else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kern_ms = np.array([a.elapsed_time(b) for a, b in evs])
+    kern_ms = np.array([a.elapsed_time(b) for a, b in evs]) if events else None
     return (t1 - t0) * 1e3 / steps, kern_ms
 
 
@@ -219,7 +227,8 @@ def main():
     layers = [Layer(pz, wl, torch, spec, seed=spec["seed"] + 1000 * r, kv_dtype=pz.KV_FP8,
                     keep_context=(r == 0 and args.cpu_seqs > 0)) for r in range(spec["instances"])]
     log("built %d FP8 cache instances in %.1f s" % (len(layers), time.perf_counter() - t_setup))
-    ms_step, kern_ms = time_steps(torch, layers, args.steps, args.warmup)
+    ms_step, _ = time_steps(torch, layers, args.steps, args.warmup, events=False)
+    ms_step_ev, kern_ms = time_steps(torch, layers, args.steps, args.warmup, events=True)
     attn_bytes = float(np.mean([l.attn_bytes(wl) for l in layers]))
     step_bytes = float(np.mean([l.step_bytes(wl) for l in layers]))
     B = spec["B"]
@@ -238,8 +247,19 @@ def main():
                      "achieved": attn_bytes / (kern_avg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": attn_bytes / (kern_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "kernel_us_avg": kern_avg_ms * 1e3, "kernel_us_std": float(kern_ms.std() * 1e3),
+                     "ms_per_step_with_events": ms_step_ev,
                      "algorithmic_bytes_per_launch": attn_bytes, "traffic": None},
     }
+    if args.workload == "cfg3" and args.split_tokens is None:
+        # the same step with the chunk length a caller free to choose would use (fewer, longer partials)
+        for l in layers:
+            l.set_split(8192)
+        ms_t, _ = time_steps(torch, layers, args.steps, args.warmup, events=False)
+        result["tuned_split"] = {"split_tokens": 8192, "ms_per_step": ms_t, "GBps": step_bytes / (ms_t * 1e-3) / 1e9,
+                                 "pct_hbm_peak": 100.0 * step_bytes / (ms_t * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                 "attn_tokens_per_s": B / (ms_t * 1e-3)}
+        for l in layers:
+            l.set_split(spec["split_tokens"])
 
     if args.cpu_seqs > 0:
         import oracle
@@ -260,7 +280,8 @@ def main():
         torch.cuda.empty_cache()
         n_inst = max(2, spec["instances"] - 1)
         bl = [Layer(pz, wl, torch, spec, seed=spec["seed"] + 1000 * r, kv_dtype=pz.KV_BF16) for r in range(n_inst)]
-        ms_b, kern_b = time_steps(torch, bl, args.steps, args.warmup)
+        ms_b, _ = time_steps(torch, bl, args.steps, args.warmup, events=False)
+        _, kern_b = time_steps(torch, bl, args.steps, args.warmup, events=True)
         sb = float(np.mean([l.step_bytes(wl) for l in bl]))
         ab = float(np.mean([l.attn_bytes(wl) for l in bl]))
         result["bf16_kv"] = {"ms_per_step": ms_b, "GBps": sb / (ms_b * 1e-3) / 1e9,

@@ -50,11 +50,12 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
         const int64_t t = t0 + (threadIdx.x >> 2);
         const int part = threadIdx.x & 3;
         if (t < prm.T) {
+            // the row is fetched beside the slot, not after it: one memory round trip, not two
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(prm.k_new + (t * Hkv + g) * 64 + part * 16);
+            const u32x4 x0 = src[0], x1 = src[1];
             const int64_t slot = prm.slot_mapping[t];
             if (slot >= 0) {
                 const int64_t page = slot / P, off = slot % P;
-                const u32x4 *src = reinterpret_cast<const u32x4 *>(prm.k_new + (t * Hkv + g) * 64 + part * 16);
-                const u32x4 x0 = src[0], x1 = src[1];
                 uint8_t *dst = prm.k + (((page * Hkv + g) * P + off) * 64 + part * 16) * EB;
                 if constexpr (EB == 1) {
                     u32x4 o;
@@ -74,13 +75,13 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
         const int64_t t = t0 + (threadIdx.x & 63);
         const int c0 = (threadIdx.x >> 6) * 16;
         if (t < prm.T) {
+            const uint16_t *src = prm.v_new + (t * Hkv + g) * 64 + c0;
+            const u32x4 x0 = reinterpret_cast<const u32x4 *>(src)[0];
+            const u32x4 x1 = reinterpret_cast<const u32x4 *>(src)[1];
             const int64_t slot = prm.slot_mapping[t];
             if (slot >= 0) {
                 const int64_t page = slot / P, off = slot % P;
-                const uint16_t *src = prm.v_new + (t * Hkv + g) * 64 + c0;
                 uint8_t *dst = prm.v + (((page * Hkv + g) * 64 + c0) * P + off) * EB;
-                const u32x4 x0 = reinterpret_cast<const u32x4 *>(src)[0];
-                const u32x4 x1 = reinterpret_cast<const u32x4 *>(src)[1];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const unsigned w = (i < 8) ? x0[i / 2] : x1[(i - 8) / 2];

@@ -62,6 +62,24 @@ __device__ __forceinline__ unsigned pack_hi16(float first, float second) {
 
 __device__ __forceinline__ float fmax3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+// Reductions over the four 16-lane rows of a wave (lanes n, n+16, n+32, n+48) without LDS:
+// v_permlane16_swap(x, x) yields (rows 0,0,2,2 | rows 1,1,3,3) and v_permlane32_swap(y, y)
+// yields (low half twice | high half twice), so two swaps and two ops reduce over the rows.
+__device__ __forceinline__ float rows_max(float x) {
+    u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+    u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 __device__ __forceinline__ float bf16_round_to_f32bits(float x, uint16_t *bits) {
     unsigned u = __float_as_uint(x);
     if ((u & 0x7fffffffu) > 0x7f800000u) { *bits = (uint16_t)((u >> 16) | 0x40u); return x; }
@@ -189,8 +207,7 @@ __device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigne
     mx = fmax3(mx, sacc[2][3], sacc[3][0]);
     mx = fmax3(mx, sacc[3][1], sacc[3][2]);
     mx = fmaxf(mx, sacc[3][3]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = rows_max(mx);
     const float m_new = fmaxf(st.m, mx * sc);          // sc > 0
     // m_new is finite here: every processed step holds at least one valid position
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
@@ -249,7 +266,7 @@ __device__ __forceinline__ float add_ror8(float x) {
 template <int P, int EB>
 __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
-    constexpr int GROUP = 64 / NPS;                    // steps whose page ids fit one register
+    constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
     // dynamic LDS in records of 528 floats (8 heads x 64 channels, then 8 m's, then 8 l's):
     // one record per wave (n_waves > 1), or one per chunk of the group (one-wave split-K)
     extern __shared__ float lds[];
@@ -269,6 +286,18 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     const int n = lane & 15, kb = lane >> 4;
     const int head = n & 7;
     const int qh = g * G + head;                       // only meaningful when head < G
+
+    // One-wave workgroups of full-attention layers know their first step without the sequence
+    // length, so their first block-table read is issued beside the read of the length instead
+    // of after it (entries past the context are replaced below, before any use).
+    const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
+    const bool early_ids = direct && prm.window == 0;
+    const int early_s0 = final_pass ? 0 : (cgrp * prm.chunks_per_group * prm.split_tokens) >> 6;
+    int early0 = 0, early1 = 0;
+    if (early_ids) {
+        early0 = bt[min(early_s0 * NPS + lane, prm.max_pages - 1)];
+        early1 = bt[min(early_s0 * NPS + 64 + lane, prm.max_pages - 1)];
+    }
 
     const int L = prm.seq_lens[b];
     const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
@@ -295,9 +324,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     // partials go to HBM in one burst when the wave is done, so that no store sits between the
     // loads of the pipeline), or write it as the final row (single pass); then reset it
     auto emit_direct = [&](int slot) {
-        float l = st.l;
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        const float l = rows_sum(st.l);
         float scale = 1.0f;
         if (final_pass) {
             const float sink2 = (prm.sinks != nullptr && head < G) ? prm.sinks[qh] * kLog2e : -INFINITY;
@@ -357,7 +384,6 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             const int64_t page_bytes = (int64_t)prm.Hkv * P * 64 * EB;
             const uint8_t *kbase = prm.k + (int64_t)g * P * 64 * EB;
             const uint8_t *vbase = prm.v + (int64_t)g * P * 64 * EB;
-            const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
             const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
             const float sc = prm.sc;
             const int steps_per_chunk = prm.split_tokens >> 6;
@@ -365,26 +391,41 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
 
             KTile<EB> kt;
             VTile<EB> vt;
-            // The wave's steps are walked in groups whose page ids sit in one register (lane i
-            // holds the physical page of page index pbase + i, clamped to attended pages).  Inside
-            // a group the K buffer is refilled right after QK^T has consumed it and the V buffer
-            // right after PV, unconditionally; the group's last step is peeled so that no load
-            // is conditional and every wait counts exactly the loads issued after the one needed.
+            // The wave's steps are walked in groups whose page ids sit in two registers (lane i of
+            // ids0 / ids1 holds the physical page of page index pbase + i / pbase + 64 + i, clamped
+            // to attended pages).  Inside a group the K buffer is refilled right after QK^T has
+            // consumed it and the V buffer right after PV, unconditionally; the group's last step
+            // is peeled so that no load is conditional and every wait counts exactly the loads
+            // issued after the one needed.
             for (int gs = s0; gs < s1; gs += GROUP) {
                 const int ge = min(gs + GROUP, s1);
                 const int pbase = gs * NPS;
-                const int ids = bt[min(max(pbase + lane, pmin), pmax)];
+                int ids0, ids1;
+                if (early_ids && gs == s0) {           // s0 == early_s0 here
+                    const int last = pmax - pbase;     // >= 0: the group holds an attended position
+                    const int fix0 = __shfl(early0, min(last, 63));
+                    const int fix1 = __shfl(early1, min(max(last - 64, 0), 63));
+                    ids0 = lane <= last ? early0 : fix0;
+                    ids1 = last < 64 ? fix0 : (lane + 64 <= last ? early1 : fix1);
+                } else {
+                    ids0 = bt[min(max(pbase + lane, pmin), pmax)];
+                    ids1 = bt[min(max(pbase + 64 + lane, pmin), pmax)];
+                }
+                auto page_id = [&](int idx) -> int {   // idx: page index relative to pbase, < 128
+                    if constexpr (NPS == 1) {
+                        const int a = __builtin_amdgcn_readlane(ids0, idx & 63);
+                        const int c = __builtin_amdgcn_readlane(ids1, idx & 63);
+                        return idx < 64 ? a : c;
+                    } else {
+                        const int a = __shfl(ids0, idx & 63), c = __shfl(ids1, idx & 63);
+                        return idx < 64 ? a : c;
+                    }
+                };
                 auto k_page = [&](int s) -> const uint8_t * {
-                    int pid;
-                    if constexpr (NPS == 1) pid = __builtin_amdgcn_readlane(ids, s - gs);
-                    else pid = __shfl(ids, s * NPS + geom.kslot - pbase);
-                    return kbase + (int64_t)pid * page_bytes;
+                    return kbase + (int64_t)page_id(s * NPS + geom.kslot - pbase) * page_bytes;
                 };
                 auto v_page = [&](int s) -> const uint8_t * {
-                    int pid;
-                    if constexpr (NPS == 1) pid = __builtin_amdgcn_readlane(ids, s - gs);
-                    else pid = __shfl(ids, s * NPS + geom.vslot - pbase);
-                    return vbase + (int64_t)pid * page_bytes;
+                    return vbase + (int64_t)page_id(s * NPS + geom.vslot - pbase) * page_bytes;
                 };
                 auto step = [&](int s, bool prefetch) {
                     const int base = s << 6;
@@ -428,26 +469,44 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         // burst the parked partials out: one 256-byte row per head and chunk, lane = channel;
         // chunks of the group that lie beyond the context are written as empty partials
         __syncthreads();                               // lanes read what other lanes parked
-        for (int c = c_first; c < c_last; ++c) {
-            const bool parked = c < next_chunk;
-            const float *src = &lds[(c - c_first) * 528];
-            for (int h = 0; h < G; ++h) {
-                const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c;
-                prm.ws_acc[row * 64 + lane] = parked ? src[h * 64 + lane] : 0.f;
-                if (lane < 2) {
-                    const float empty_ml = lane == 0 ? -INFINITY : 0.f;
-                    prm.ws_ml[row * 2 + lane] = parked ? src[512 + 8 * lane + h] : empty_ml;
+        // 16 lanes cover one 256-byte row; a wave-wide store covers 4 rows
+        const int n_rows = (c_last - c_first) * G;
+        const int quad = lane & 15;
+        for (int r0 = 0; r0 < n_rows; r0 += 16) {
+            f32x4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = min(r0 + 4 * u + (lane >> 4), n_rows - 1);
+                const int cl = r / G, h = r - cl * G;
+                x[u] = *reinterpret_cast<const f32x4 *>(&lds[cl * 528 + h * 64 + 4 * quad]);
+                if (c_first + cl >= next_chunk) x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = r0 + 4 * u + (lane >> 4);
+                if (r < n_rows) {
+                    const int cl = r / G, h = r - cl * G;
+                    const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c_first + cl;
+                    *reinterpret_cast<f32x4 *>(prm.ws_acc + row * 64 + 4 * quad) = x[u];
                 }
             }
+        }
+        // (m, l) pairs: one lane per (chunk, head)
+        for (int r = lane; r < n_rows; r += 64) {
+            const int cl = r / G, h = r - cl * G;
+            const bool parked = c_first + cl < next_chunk;
+            const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c_first + cl;
+            float2 ml;
+            ml.x = parked ? lds[cl * 528 + 512 + h] : -INFINITY;
+            ml.y = parked ? lds[cl * 528 + 520 + h] : 0.f;
+            *reinterpret_cast<float2 *>(prm.ws_ml + row * 2) = ml;
         }
         return;
     }
 
     // n_waves > 1: per-wave result -> LDS (add the two P halves, sum the denominator over the
     // four lane groups), then merge and write the final row or the sink-free partial
-    float l = st.l;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
+    const float l = rows_sum(st.l);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -507,29 +566,37 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // Merge kernel: one wave per (sequence, query head).  The chunks are taken 64 at a time: lane i
 // fetches (m_i, l_i) of chunk i and computes its weight exp(m_i - M); then lane = channel and the
-// 64 accumulator rows are streamed with 16 independent loads in flight per lane, each scaled by
-// its chunk's weight read out of the weight register (uniform lane index).
+// 64 accumulator rows are streamed, all 64 loads of a lane in flight together, each row scaled by
+// its chunk's weight read out of the weight register (uniform lane index).  The first batch is
+// fetched before the sequence length is known: every chunk row of the workspace is written by the
+// first pass (empty partials have weight 0), so reading past a short sequence's chunks is safe.
 __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
     const int lane = threadIdx.x;
-    int n = prm.n_splits;
-    if (prm.seq_lens != nullptr) {
-        const int L = prm.seq_lens[b];
-        const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
-        const int span = L - (lo & ~63);
-        n = min(n, (span + prm.split_tokens - 1) / prm.split_tokens);
-    }
-    const float *acc = prm.ws_acc + (int64_t)row * prm.n_splits * 64;
-    const float2 *ml = reinterpret_cast<const float2 *>(prm.ws_ml) + (int64_t)row * prm.n_splits;
+    const int S = prm.n_splits;
+    const float *acc = prm.ws_acc + (int64_t)row * S * 64;
+    const float2 *ml = reinterpret_cast<const float2 *>(prm.ws_ml) + (int64_t)row * S;
     const float sink = prm.sinks != nullptr ? prm.sinks[h] : -INFINITY;
     float M = sink;                                    // running reference maximum
     float num = 0.f;
     float den = (sink == -INFINITY) ? 0.f : 1.0f;      // exp(sink - M) with M == sink
+    int n = S;
     for (int base = 0; base < n; base += 64) {
-        const int cnt = min(64, n - base);
+        const int cnt = min(64, S - base);             // rows that exist
         float2 v = {-INFINITY, 0.f};
         if (lane < cnt) v = ml[base + lane];
+        const float *a = acc + (int64_t)base * 64 + lane;
+        float x[64];
+#pragma unroll
+        for (int u = 0; u < 64; ++u) x[u] = a[(int64_t)min(u, cnt - 1) * 64];
+        if (base == 0 && prm.seq_lens != nullptr) {    // chunks past this bound are empty by construction
+            const int L = prm.seq_lens[b];
+            const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
+            const int span = L - (lo & ~63);
+            n = min(S, (span + prm.split_tokens - 1) / prm.split_tokens);
+        }
+        if (base + lane >= n) v.x = -INFINITY;
         const float M_new = fmaxf(M, wave_max(v.x));
         if (M_new == -INFINITY) continue;              // only empty partials so far, no sink
         const float keep = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((M - M_new) * kLog2e);
@@ -537,16 +604,10 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParam
         num *= keep;
         den = den * keep + wave_sum(v.y * w);
         M = M_new;
-        const float *a = acc + (int64_t)base * 64 + lane;
-        for (int k = 0; k < cnt; k += 16) {
-            float x[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) x[u] = a[(int64_t)min(k + u, cnt - 1) * 64];
-#pragma unroll
-            for (int u = 0; u < 16; ++u) {
-                const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), min(k + u, 63)));
-                num = __builtin_fmaf(x[u], (k + u < cnt) ? wu : 0.f, num);
-            }
+        for (int u = 0; u < 64; ++u) {
+            const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
+            num = __builtin_fmaf(x[u], wu, num);       // rows >= cnt repeat row cnt-1 with weight 0
         }
     }
     const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
