@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 
 import numpy as np  # noqa: E402
 
+# HBM bytes per decode_attn launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/decode_step_cfg3_fp8_hbm_traffic.txt:
+# counters scaled by what they read for a plain 768 MiB copy); only measured for the default cfg3 launch.
+MEASURED_TRAFFIC_BYTES = {"cfg3": 1091883524}
+
 METRIC = "decode-attention GB/s (% of HBM peak) + attn tokens/s, B=16 ctx=64K FP8 KV"
 HBM_PEAK_GBPS = 8000.0
 
@@ -204,6 +208,8 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-bf16", action="store_true", help="skip the BF16-KV comparison run")
     ap.add_argument("--split-tokens", type=int, default=None, help="override the workload's split-K chunk length")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 768 MiB device-to-device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (the path needs no collective; see DESIGN.md on sharding): "
@@ -223,6 +229,13 @@ def main():
         spec["text"] += " [split_tokens overridden to %d]" % args.split_tokens
     torch.cuda.set_device(0)
 
+    if args.calib_copy:
+        src = torch.ones((768 << 20) // 4, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     t_setup = time.perf_counter()
     layers = [Layer(pz, wl, torch, spec, seed=spec["seed"] + 1000 * r, kv_dtype=pz.KV_FP8,
                     keep_context=(r == 0 and args.cpu_seqs > 0)) for r in range(spec["instances"])]
@@ -248,7 +261,8 @@ def main():
                      "frac": attn_bytes / (kern_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "kernel_us_avg": kern_avg_ms * 1e3, "kernel_us_std": float(kern_ms.std() * 1e3),
                      "ms_per_step_with_events": ms_step_ev,
-                     "algorithmic_bytes_per_launch": attn_bytes, "traffic": None},
+                     "algorithmic_bytes_per_launch": attn_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.split_tokens is None else None},
     }
     if args.workload == "cfg3" and args.split_tokens is None:
         # the same step with the chunk length a caller free to choose would use (fewer, longer partials)
