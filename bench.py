@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the decode-attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4_w128|cfg4_w8192]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|cfg4_w128|cfg4_w8192|cfg5]
 
 A step is one pass of the whole path over one batch: quantise-and-append of one new token per
 sequence, decode attention (split-K partials + log-sum-exp merge, or single pass for short
@@ -46,6 +46,20 @@ WORKLOADS = {
     "cfg4_w8192": dict(B=256, L=(1024, 65536), window=8192, split_tokens=1024, outlier_frac=0.0, seed=4,
                        instances=2,
                        text="cfg4: batch 256, ragged contexts U[1024,65536], sliding window 8192, split-K 1024"),
+    # diagnostics: uniform lengths at twice cfg3's batch, and cfg3's batch with ragged lengths
+    "diag_b32_uniform": dict(B=32, L=65536, window=0, split_tokens=1024, outlier_frac=0.0, seed=7, instances=3,
+                             text="diagnostic: batch 32 x context 65536, split-K 1024"),
+    "diag_b8_128k": dict(B=8, L=131072, window=0, split_tokens=1024, outlier_frac=0.0, seed=8, instances=4,
+                         text="diagnostic: batch 8 x context 131072, split-K 1024"),
+    "diag_b16_ragged": dict(B=16, L=(1024, 131072), window=0, split_tokens=1024, outlier_frac=0.0, seed=5, instances=4,
+                            text="diagnostic: batch 16, ragged contexts U[1024,131072], split-K 1024"),
+    # single layers of the heterogeneous step (cfg5), for tests and tuning
+    "cfg5_full": dict(B=32, L=(1024, 131072), window=0, split_tokens=1024, outlier_frac=0.0, seed=5, instances=3,
+                      bounded=True, text="cfg5 full-attention layer: batch 32, ragged contexts U[1024,131072], split-K 1024"),
+    "cfg5_w8192": dict(B=32, L=(1024, 131072), window=8192, split_tokens=1024, outlier_frac=0.0, seed=5, instances=3,
+                       bounded=True, text="cfg5 window-8192 layer: batch 32, ragged contexts U[1024,131072], split-K 1024"),
+    "cfg5_w128": dict(B=32, L=(1024, 131072), window=128, split_tokens=0, outlier_frac=0.0, seed=5, instances=3,
+                      bounded=True, text="cfg5 window-128 layer: batch 32, ragged contexts U[1024,131072], single pass"),
 }
 
 
@@ -60,13 +74,18 @@ class Layer:
         B = spec["B"]
         if isinstance(spec["L"], tuple):
             seq_lens = wl.ragged_lengths(spec["seed"], B, *spec["L"])
+            if os.environ.get("PZ_BENCH_ROUND_LENS"):             # diagnostic: round the ragged lengths up
+                r = int(os.environ["PZ_BENCH_ROUND_LENS"])
+                seq_lens = ((seq_lens + r - 1) // r * r).astype(np.int32)
         else:
             seq_lens = np.full(B, spec["L"], dtype=np.int32)
         self.pz, self.torch = pz, torch
         self.window, self.split = spec["window"], spec["split_tokens"]
         self.kv_dtype = kv_dtype
+        # a window layer keeps only the pages its window can touch (spec["bounded"])
+        resident = self.window + 64 if (spec.get("bounded") and self.window > 0) else None
         lay = wl.device_layer(B=B, seq_lens=seq_lens, window=self.window, seed=seed,
-                              outlier_frac=spec["outlier_frac"])
+                              outlier_frac=spec["outlier_frac"], resident=resident)
         self.lay = lay
         self.k_scale = lay.k_scale if kv_dtype == pz.KV_FP8 else 1.0
         self.v_scale = lay.v_scale if kv_dtype == pz.KV_FP8 else 1.0
@@ -157,36 +176,45 @@ def time_steps(torch, layers, steps, warmup, events):
     return (t1 - t0) * 1e3 / steps, kern_ms
 
 
-def cpu_baseline(pz, wl, oracle, torch, layer, n_seq):
-    """The oracle, as it stands, on the first n_seq sequences of instance 0 (all query heads):
-    its own quantise-and-append of their whole context (set-up, untimed), then timed: append of
-    the new tokens + unsplit attention.  Returns the baseline dict and the oracle rows."""
+def oracle_sample(oracle, torch, layer, seqs):
+    """Oracle-side copy of the listed sequences of a Layer: its own cache (compact page numbering,
+    its own layout) filled by the oracle's quantise-and-append from the same bf16 K/V, all but the
+    newest token of each sequence.  Returns (kc, vc, block_table, q_bits, new_k, new_v, new_slots)."""
     lay = layer.lay
-    cores = min(len(os.sched_getaffinity(0)), 16)
-    off = np.concatenate([[0], np.cumsum(lay.seq_lens.astype(np.int64))])
     P = lay.P
-    n_pages = [-(-int(lay.seq_lens[b]) // P) for b in range(n_seq)]
-    bt = np.full((n_seq, max(n_pages)), -1, dtype=np.int32)
+    off, fp = lay.ctx_offsets, lay.first_pos
+    end_page = [-(-int(lay.seq_lens[b]) // P) for b in seqs]
+    bt = np.full((len(seqs), max(end_page)), -1, dtype=np.int32)
     at = 0
-    for b in range(n_seq):                                        # compact page numbering for the sample
-        bt[b, :n_pages[b]] = np.arange(at, at + n_pages[b])
-        at += n_pages[b]
+    for i, b in enumerate(seqs):
+        p0 = int(fp[b]) // P
+        bt[i, p0:end_page[i]] = np.arange(at, at + end_page[i] - p0)
+        at += end_page[i] - p0
     kc, vc = oracle.new_cache(at * P, lay.Hkv, lay.d, oracle.KV_FP8)
     new_k, new_v, new_slots = [], [], []
-    for b in range(n_seq):
-        L = int(lay.seq_lens[b])
+    for i, b in enumerate(seqs):
         kb = lay.k_ctx[off[b]:off[b + 1]].view(torch.int16).cpu().numpy().view(np.uint16)
         vb = lay.v_ctx[off[b]:off[b + 1]].view(torch.int16).cpu().numpy().view(np.uint16)
-        j = np.arange(L, dtype=np.int64)
-        slots = bt[b, j // P].astype(np.int64) * P + j % P
+        j = np.arange(int(fp[b]), int(lay.seq_lens[b]), dtype=np.int64)
+        slots = bt[i, j // P].astype(np.int64) * P + j % P
         oracle.kv_append(kc, vc, kb[:-1], vb[:-1], slots[:-1], lay.k_scale, lay.v_scale)
         new_k.append(kb[-1:]); new_v.append(vb[-1:]); new_slots.append(slots[-1:])
-    q = lay.q[:n_seq].view(torch.int16).cpu().numpy().view(np.uint16)
+    q = lay.q[torch.as_tensor(list(seqs), device=lay.q.device)].view(torch.int16).cpu().numpy().view(np.uint16)
+    return kc, vc, bt, q, np.concatenate(new_k), np.concatenate(new_v), np.concatenate(new_slots)
+
+
+def cpu_baseline(pz, wl, oracle, torch, layer, n_seq):
+    """The oracle, as it stands, on the first n_seq sequences of a Layer (all query heads): its
+    own quantise-and-append of their context (set-up, untimed), then timed: append of the new
+    tokens + unsplit attention.  Returns the baseline dict and the oracle rows."""
+    lay = layer.lay
+    cores = min(len(os.sched_getaffinity(0)), 16)
+    seqs = list(range(n_seq))
+    kc, vc, bt, q, new_k, new_v, new_slots = oracle_sample(oracle, torch, layer, seqs)
     sinks = lay.sinks.cpu().numpy()
     t0 = time.perf_counter()
-    oracle.kv_append(kc, vc, np.concatenate(new_k), np.concatenate(new_v), np.concatenate(new_slots),
-                     lay.k_scale, lay.v_scale)
-    want = oracle.decode_attn(kc, vc, P, q, bt, lay.seq_lens[:n_seq], sinks, lay.sm_scale, lay.k_scale,
+    oracle.kv_append(kc, vc, new_k, new_v, new_slots, lay.k_scale, lay.v_scale)
+    want = oracle.decode_attn(kc, vc, lay.P, q, bt, lay.seq_lens[:n_seq], sinks, lay.sm_scale, lay.k_scale,
                               lay.v_scale, layer.window, nthreads=cores)
     dt = time.perf_counter() - t0
     toks = wl.kv_tokens_read(lay.seq_lens[:n_seq], layer.window)
@@ -199,12 +227,121 @@ def cpu_baseline(pz, wl, oracle, torch, layer, n_seq):
     return base, want
 
 
+class Model:
+    """The heterogeneous 36-layer decode step: every layer appends one token per sequence and runs
+    its attention (window 128: single pass; window 8192 and full: split-K 1024 + merge)."""
+
+    def __init__(self, pz, wl, torch, kv_dtype, keep_context_types=()):
+        self.pattern = wl.layer_pattern(seed=5)
+        self.layers = []
+        kept = set()
+        for i, w in enumerate(self.pattern):
+            spec = dict(B=32, L=(1024, 131072), window=w, split_tokens=0 if w == 128 else 1024,
+                        outlier_frac=0.0, seed=5, bounded=True)
+            keep = w in keep_context_types and w not in kept
+            kept.add(w) if keep else None
+            self.layers.append(Layer(pz, wl, torch, spec, seed=5 + 1000 * (i + 1), kv_dtype=kv_dtype,
+                                     keep_context=keep))
+        self.full = [l for l in self.layers if l.window == 0]
+
+    def step(self, ev=None):
+        k = 0
+        for l in self.layers:
+            if ev is not None and l.window == 0:
+                l.step(ev[k])
+                k += 1
+            else:
+                l.step()
+
+
+def time_model(torch, model, steps, warmup, events):
+    for _ in range(warmup):
+        model.step()
+    n_full = len(model.full)
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_full)]
+           for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        model.step(evs[i] if events else None)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kern = np.array([[a.elapsed_time(b) for a, b in e] for e in evs]) if events else None
+    return (t1 - t0) * 1e3 / steps, kern
+
+
+def run_cfg5(args, pz, wl, torch):
+    """36 layers: 18 x window 128, 8 x window 8192, 10 x full; batch 32, contexts U[1024,131072]."""
+    text = ("cfg5: 36-layer decode step (18 x window-128, 8 x window-8192, 10 x full attention), batch 32, ragged "
+            "contexts U[1024,131072], 64 q / 8 KV heads, d=64, paged E4M3 KV with per-layer K/V scales; every layer "
+            "= kv_append of 1 token/seq + decode attention (+ LSE merge)")
+    t0 = time.perf_counter()
+    model = Model(pz, wl, torch, pz.KV_FP8, keep_context_types=(128, 8192, 0) if args.cpu_seqs > 0 else ())
+    log("built the 36 FP8 layer caches in %.1f s" % (time.perf_counter() - t0))
+    ms_step, _ = time_model(torch, model, args.steps, args.warmup, events=False)
+    ms_ev, kern = time_model(torch, model, args.steps, args.warmup, events=True)
+    step_bytes = float(sum(l.step_bytes(wl) for l in model.layers))
+    full_bytes = float(np.mean([l.attn_bytes(wl) for l in model.full]))
+    kern_avg = float(kern.mean())
+    B = 32
+    by_type = {}
+    for w in (128, 8192, 0):
+        ls = [l for l in model.layers if l.window == w]
+        by_type["full" if w == 0 else "window_%d" % w] = {"layers": len(ls),
+                                                             "kv_bytes_per_layer": float(ls[0].attn_bytes(wl))}
+    result = {
+        "metric": "decode-attention GB/s (% of HBM peak) + attn tokens/s, 36-layer heterogeneous step B=32 FP8 KV",
+        "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "e4m3 KV -> bf16 MFMA operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": text, "batch": B, "layers": by_type},
+        "attn_tokens_per_s": B / (ms_step * 1e-3),
+        "pct_hbm_peak": 100.0 * step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel<64,1> (the 10 full-attention layers)",
+                     "achieved": full_bytes / (kern_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": full_bytes / (kern_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, "kernel_us_avg": kern_avg * 1e3,
+                     "ms_per_step_with_events": ms_ev, "algorithmic_bytes_per_launch": full_bytes, "traffic": None},
+    }
+    if args.cpu_seqs > 0:
+        import oracle
+        n_seq = min(args.cpu_seqs, B)
+        tot_t, tot_b, worst, cores = 0.0, 0.0, 0.0, 0
+        for w in (128, 8192, 0):
+            ls = [l for l in model.layers if l.window == w]
+            l0 = next(l for l in ls if l.lay.k_ctx is not None)
+            l0.step()
+            torch.cuda.synchronize()
+            got = l0.out[:n_seq].cpu().numpy()
+            base, want = cpu_baseline(pz, wl, oracle, torch, l0, n_seq)
+            rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
+            worst = max(worst, float(np.max(np.abs(got - want)) / rms))
+            tot_t += len(ls) * base["seconds"]
+            tot_b += len(ls) * base["value"] * 1e9 * base["seconds"]
+            cores = base["cores"]
+            l0.lay.k_ctx = l0.lay.v_ctx = None
+        result["cpu_baseline"] = {"value": tot_b / tot_t / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
+                                  "seconds_scaled_to_36_layers": tot_t, "parity_max_abs_over_rms": worst,
+                                  "sample": "first %d of 32 sequences of one layer of each type (window 128, window "
+                                            "8192, full), timed once and weighted by the 18/8/10 layer counts" % n_seq}
+    else:
+        result["cpu_baseline"] = None
+    if not args.no_bf16:
+        del model
+        torch.cuda.empty_cache()
+        mb = Model(pz, wl, torch, pz.KV_BF16)
+        ms_b, _ = time_model(torch, mb, args.steps, args.warmup, events=False)
+        sb = float(sum(l.step_bytes(wl) for l in mb.layers))
+        result["bf16_kv"] = {"ms_per_step": ms_b, "GBps": sb / (ms_b * 1e-3) / 1e9,
+                             "attn_tokens_per_s": B / (ms_b * 1e-3), "fp8_speedup_tokens_per_s": ms_b / ms_step}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS) + ["cfg5"])
     ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-bf16", action="store_true", help="skip the BF16-KV comparison run")
     ap.add_argument("--split-tokens", type=int, default=None, help="override the workload's split-K chunk length")
@@ -223,6 +360,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     pz.lib()                                                      # fails loudly if libpz.so is not built
+    torch.cuda.set_device(0)
+    if args.workload == "cfg5":
+        return run_cfg5(args, pz, wl, torch)
     spec = dict(WORKLOADS[args.workload])
     if args.split_tokens is not None:
         spec["split_tokens"] = args.split_tokens
@@ -247,7 +387,8 @@ def main():
     B = spec["B"]
     kern_avg_ms = float(kern_ms.mean())
     result = {
-        "metric": METRIC, "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "metric": METRIC if args.workload == "cfg3" else METRIC.split(", B=16")[0] + ", " + args.workload + " FP8 KV",
+        "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "e4m3 KV -> bf16 MFMA operands, f32 accumulate",
         "data": "synthetic",

@@ -143,15 +143,19 @@ def kv_append(k_cache, v_cache, k_new_bits, v_new_bits, slot_mapping, k_scale, v
                         T, float(k_scale), float(v_scale))
 
 
-def _check_tables(k_cache, P, block_table, seq_lens):
+def _check_tables(k_cache, P, block_table, seq_lens, window=0):
+    """Every page that holds an attended position must be a valid physical page."""
     B, max_pages = block_table.shape
     assert seq_lens.shape == (B,)
     num_pages = k_cache.shape[0] // P
     for b in range(B):
-        n = -(-int(seq_lens[b]) // P)
+        L = int(seq_lens[b])
+        n = -(-L // P)
         assert n <= max_pages
         if n:
-            assert 0 <= block_table[b, :n].min() and block_table[b, :n].max() < num_pages
+            lo = L - window if (window > 0 and L > window) else 0
+            used = block_table[b, lo // P:n]
+            assert 0 <= used.min() and used.max() < num_pages
 
 
 def decode_attn(k_cache, v_cache, P, q_bits, block_table, seq_lens, sinks, sm_scale, k_scale,
@@ -166,7 +170,7 @@ def decode_attn(k_cache, v_cache, P, q_bits, block_table, seq_lens, sinks, sm_sc
     assert dq == d and Hq % Hkv == 0
     bt = _req(block_table, np.int32)
     sl = _req(seq_lens, np.int32)
-    _check_tables(k_cache, P, bt, sl)
+    _check_tables(k_cache, P, bt, sl, window)
     sk = None if sinks is None else _req(sinks, np.float32)
     out = np.zeros((B, Hq, d), dtype=np.float32)
     r = None if rows is None else _req(rows, np.int32)
@@ -186,7 +190,7 @@ def decode_attn_partials(k_cache, v_cache, P, q_bits, block_table, seq_lens, sm_
     B, Hq, _ = q.shape
     bt = _req(block_table, np.int32)
     sl = _req(seq_lens, np.int32)
-    _check_tables(k_cache, P, bt, sl)
+    _check_tables(k_cache, P, bt, sl, window)
     acc = np.zeros((B, Hq, n_splits, d), dtype=np.float32)
     ml = np.zeros((B, Hq, n_splits, 2), dtype=np.float32)
     lib().pzo_decode_attn_partials(_p(k_cache), _p(v_cache), kv_dtype, P, Hkv, d, _p(q), _p(bt),

@@ -24,7 +24,7 @@
 //     operand is again a direct 8-byte slice of what was loaded.  P is fed as bf16 in two
 //     terms: columns 0..7 carry the top 8 significant bits of p, columns 8..15 the next 8, which
 //     keeps p to ~2^-16 relative; the two halves are added at the end.  The softmax
-//     denominator is accumulated from the unsplit fp32 p.
+//     denominator comes out of the same instruction: a row of ones sums the same bf16 weights.
 //   * Waves of a workgroup own disjoint step ranges and are merged through LDS (2 KiB per
 //     wave); the workgroup then writes either a sink-free partial (split-K) or the final row.
 #include <hip/hip_runtime.h>
@@ -181,7 +181,7 @@ __device__ __forceinline__ void mask_v(VTile<EB> &tile, unsigned valid) {
 
 struct WaveState {
     float m;          // running maximum of the log2-scaled logits of this lane's head column
-    float l;          // this lane's share of the denominator (its own 16 positions per step)
+    f32x4 l;          // denominator share of the lane's column (P half), every element the same
     f32x4 o[4];       // O^T: channel 16*c + 4*kb + r of the lane's head column
 };
 
@@ -213,18 +213,15 @@ __device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigne
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
     st.m = m_new;
     float p[16];
-    float psum = 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
+        for (int r = 0; r < 4; ++r)
             p[4 * j + r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j][r], sc, -m_new));
-            psum += p[4 * j + r];
-        }
-    st.l = st.l * alpha + psum;
     if (__any(alpha != 1.0f)) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) st.o[c] *= alpha;
+        st.l *= alpha;
     }
     // P^T operand: head columns 0..7 take the top bf16 of p, columns 8..15 the remainder
 #pragma unroll
@@ -235,8 +232,15 @@ __device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigne
     }
 }
 
+// O^T += V^T P^T, and the softmax denominator by the same instruction: a 17th "channel" whose
+// V row is all ones sums the very bf16 weights that multiply V, so numerator and denominator
+// share their rounding (every row of that product is the same sum over the step's 64 positions).
 template <int EB>
 __device__ __forceinline__ void pv_step(const VTile<EB> &tile, const u32x4 (&pw)[2], WaveState &st) {
+    const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};       // bf16 1.0
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+    st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, __builtin_bit_cast(bf16x8, pw[0]), st.l, 0, 0, 0);
+    st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, __builtin_bit_cast(bf16x8, pw[1]), st.l, 0, 0, 0);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
         st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<EB>(tile, c, 0),
@@ -314,7 +318,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     WaveState st;
     auto reset_state = [&]() {
         st.m = -INFINITY;
-        st.l = 0.f;
+        st.l = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < 4; ++c) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     };
@@ -324,7 +328,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     // partials go to HBM in one burst when the wave is done, so that no store sits between the
     // loads of the pipeline), or write it as the final row (single pass); then reset it
     auto emit_direct = [&](int slot) {
-        const float l = rows_sum(st.l);
+        const float l = add_ror8(st.l[0]);           // both P halves, all 64 positions of every step
         float scale = 1.0f;
         if (final_pass) {
             const float sink2 = (prm.sinks != nullptr && head < G) ? prm.sinks[qh] * kLog2e : -INFINITY;
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
 
     // n_waves > 1: per-wave result -> LDS (add the two P halves, sum the denominator over the
     // four lane groups), then merge and write the final row or the sink-free partial
-    const float l = rows_sum(st.l);
+    const float l = add_ror8(st.l[0]);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
 #pragma unroll

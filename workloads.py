@@ -75,27 +75,32 @@ class Case:
 
 
 def paged_tables(rng: np.random.Generator, seq_lens: np.ndarray, P: int, spare_pages: int = 2,
-                 min_max_pages: int = 1):
+                 min_max_pages: int = 1, first_pos=None):
     """Random page assignment: a permutation of the physical pages, dealt to the sequences.
 
-    Returns (num_pages, block_table int32 [B][max_pages], slot_mapping int64 [sum L]).
-    Unused block-table entries hold -1; `spare_pages` pages belong to no sequence."""
+    Returns (num_pages, block_table int32 [B][max_pages], slot_mapping int64 [sum (L - first_pos)]).
+    Only the pages that hold positions [first_pos_b, L_b) exist (first_pos_b a multiple of P,
+    default 0: the whole context); every other block-table entry holds -1; `spare_pages` pages
+    belong to no sequence.  The slot mapping lists the resident positions, sequence by sequence."""
     seq_lens = np.asarray(seq_lens, dtype=np.int64)
-    n_pages = (seq_lens + P - 1) // P
+    first_pos = np.zeros_like(seq_lens) if first_pos is None else np.asarray(first_pos, dtype=np.int64)
+    assert np.all(first_pos % P == 0) and np.all(first_pos <= seq_lens)
+    end_page = (seq_lens + P - 1) // P
+    n_pages = end_page - first_pos // P
     total = int(n_pages.sum())
     num_pages = total + spare_pages
     perm = rng.permutation(num_pages).astype(np.int32)
-    max_pages = max(int(n_pages.max(initial=0)), min_max_pages)
+    max_pages = max(int(end_page.max(initial=0)), min_max_pages)
     bt = np.full((len(seq_lens), max_pages), -1, dtype=np.int32)
-    slots = np.empty(int(seq_lens.sum()), dtype=np.int64)
+    slots = np.empty(int((seq_lens - first_pos).sum()), dtype=np.int64)
     at, tok = 0, 0
     for b, L in enumerate(seq_lens):
-        n = int(n_pages[b])
-        bt[b, :n] = perm[at:at + n]
+        n, p0 = int(n_pages[b]), int(first_pos[b]) // P
+        bt[b, p0:p0 + n] = perm[at:at + n]
         at += n
-        j = np.arange(int(L), dtype=np.int64)
-        slots[tok:tok + int(L)] = bt[b, j // P].astype(np.int64) * P + j % P
-        tok += int(L)
+        j = np.arange(int(first_pos[b]), int(L), dtype=np.int64)
+        slots[tok:tok + len(j)] = bt[b, j // P].astype(np.int64) * P + j % P
+        tok += len(j)
     return num_pages, bt, slots
 
 
@@ -215,24 +220,31 @@ class DeviceLayer:
     new_slots: object                     # int64 [B]: slot of each sequence's last (new) token
     k_new: object                         # bf16 [B][Hkv][d]: the new token's K rows
     v_new: object
-    k_ctx: object = None
+    first_pos: np.ndarray = None          # int64 [B]: first resident position of each sequence
+    ctx_offsets: np.ndarray = None        # int64 [B+1]: row offsets of the sequences in k_ctx / v_ctx
+    k_ctx: object = None                  # bf16 [sum (L - first_pos)][Hkv][d]: the resident positions
     v_ctx: object = None
 
 
 def device_layer(*, B, Hq=64, Hkv=8, d=64, P=64, seq_lens, window=0, seed=0, outlier_frac=0.0,
-                 outlier_gain=20.0, device="cuda"):
+                 outlier_gain=20.0, device="cuda", resident=None):
     """Device-side twin of make_case for sizes that do not fit a host round trip comfortably.
 
     Same recipe (N(0,1) -> bf16, sinks ~ N(0,1), outlier channels, amax/448 scales, random page
     permutation), drawn from torch's seeded device generator instead of numpy's, so the values
     differ from make_case's but the distribution and structure are the same.  The caller appends
-    k_ctx / v_ctx through the library and hands sampled sequences to the oracle."""
+    k_ctx / v_ctx through the library and hands sampled sequences to the oracle.
+
+    resident: keep only the pages that hold the last `resident` positions of every sequence (a
+    window layer's cache is bounded by its window); None keeps the whole context."""
     import torch
     g = torch.Generator(device=device)
     g.manual_seed(seed)
     rng = np.random.default_rng(seed)
     seq_lens = np.asarray(seq_lens, dtype=np.int32)
-    T = int(seq_lens.astype(np.int64).sum())
+    L64 = seq_lens.astype(np.int64)
+    first_pos = np.zeros(B, dtype=np.int64) if resident is None else (np.maximum(L64 - resident, 0) // P) * P
+    T = int((L64 - first_pos).sum())
     q = torch.randn((B, Hq, d), generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
     sinks = torch.randn((Hq,), generator=g, device=device, dtype=torch.float32)
     k = torch.empty((T, Hkv, d), dtype=torch.bfloat16, device=device)
@@ -251,10 +263,11 @@ def device_layer(*, B, Hq=64, Hkv=8, d=64, P=64, seq_lens, window=0, seed=0, out
     v_amax = float(v.abs().max().float().item()) if T else 0.0
     k_scale = float(np.float32(k_amax) / np.float32(E4M3_MAX)) or 1.0
     v_scale = float(np.float32(v_amax) / np.float32(E4M3_MAX)) or 1.0
-    num_pages, bt, slots = paged_tables(rng, seq_lens, P)
-    last = np.cumsum(seq_lens.astype(np.int64)) - 1
+    num_pages, bt, slots = paged_tables(rng, seq_lens, P, first_pos=first_pos)
+    ctx_offsets = np.concatenate([[0], np.cumsum(L64 - first_pos)])
+    last = ctx_offsets[1:] - 1
     last_dev = torch.from_numpy(last).to(device)
-    return DeviceLayer(B=B, Hq=Hq, Hkv=Hkv, d=d, P=P, window=window, sm_scale=float(1.0 / np.sqrt(d)),
+    return DeviceLayer(first_pos=first_pos, ctx_offsets=ctx_offsets, B=B, Hq=Hq, Hkv=Hkv, d=d, P=P, window=window, sm_scale=float(1.0 / np.sqrt(d)),
                        seq_lens=seq_lens, k_scale=k_scale, v_scale=v_scale, num_pages=num_pages,
                        block_table_host=bt, slot_mapping_host=slots, q=q, sinks=sinks,
                        block_table=torch.from_numpy(bt).to(device),
