@@ -110,6 +110,8 @@ class Layer:
         pz, lay = self.pz, self.lay
         self.split = split_tokens
         self.S = pz.pz_decode_attn_n_splits(int(lay.seq_lens.max()), self.window, self.split) if self.split else 0
+        if self.split and os.environ.get("PZ_BENCH_EXTRA_SPLITS"):   # diagnostic: surplus (empty) chunks
+            self.S += int(os.environ["PZ_BENCH_EXTRA_SPLITS"])
         self.ws_bytes = pz.pz_decode_attn_workspace_bytes(lay.B, lay.Hq, lay.d, self.S) if self.split else 0
         self.ws = self.torch.empty((max(self.ws_bytes, 4) // 4,), dtype=self.torch.float32, device="cuda")
 

@@ -122,19 +122,22 @@ size_t pz_decode_attn_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t 
  *
  *   q            : bf16 [batch][n_q_heads][head_dim]
  *   block_table  : int32 [batch][max_pages_per_seq]; entry p of row b is the physical page of
- *                  positions [p*page_size, (p+1)*page_size); only entries that hold attended
- *                  positions are read
+ *                  positions [p*page_size, (p+1)*page_size); any entry of a row may be read, but
+ *                  only entries that hold attended positions are used (the others may hold
+ *                  anything, e.g. -1)
  *   seq_lens     : int32 [batch], L_b, counting the token appended in this step
  *   sinks        : fp32 [n_q_heads] or NULL
  *   sm_scale, k_scale, v_scale : > 0
  *   window       : 0 = full attention, else sliding window length
  *   split_tokens : 0 = single pass: the sink is applied and `out` is written
  *                  (workspace may be NULL, n_splits is ignored);
- *                  > 0 (a multiple of 64) = split-K: only the partials of the n_splits chunks
- *                  defined at pz_decode_attn_n_splits are written to `workspace`, `out` is not
- *                  touched, and the caller enqueues pz_decode_attn_splitk_reduce on the same
- *                  stream.  Positions beyond n_splits * split_tokens of a_b are ignored, so
- *                  n_splits must be at least pz_decode_attn_n_splits(max_b L_b, ...).
+ *                  > 0 (a multiple of 64) = split-K: only partials are written to `workspace`
+ *                  (chunks as defined at pz_decode_attn_n_splits; a chunk that holds no attended
+ *                  position of its sequence is NOT written -- its workspace rows keep whatever
+ *                  they held), `out` is not touched, and the caller enqueues
+ *                  pz_decode_attn_splitk_reduce with the same seq_lens / window / split_tokens
+ *                  on the same stream.  Positions beyond n_splits * split_tokens of a_b are
+ *                  ignored, so n_splits must be at least pz_decode_attn_n_splits(max_b L_b, ...).
  *   out          : [batch][n_q_heads][head_dim], fp32 or bf16 (round to nearest even)
  */
 pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
@@ -149,9 +152,10 @@ pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
  *     M = max(sink_h, max_i m_i);  D = exp(sink_h - M) + sum_i l_i exp(m_i - M)
  *     out[b][h][c] = v_scale * sum_i acc_i[c] exp(m_i - M) / D
  * Empty partials (m = -inf) contribute nothing; a row whose partials are all empty is 0 (also
- * without a sink -- never NaN).  seq_lens / window / split_tokens, when seq_lens != NULL, only
- * bound how many leading chunks of each row are read (the others are empty by construction);
- * with seq_lens == NULL all n_splits partials are read.
+ * without a sink -- never NaN).  With seq_lens != NULL (and the window / split_tokens of the first
+ * pass) only the chunks that hold attended positions of a sequence are used -- exactly those the
+ * first pass wrote; whatever the other workspace rows hold is ignored.  With seq_lens == NULL all
+ * n_splits partials of every row are used, so all of them must be valid.
  */
 pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_bytes, int32_t batch,
                                        int32_t n_q_heads, int32_t head_dim, int32_t n_splits,

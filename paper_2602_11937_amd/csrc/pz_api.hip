@@ -34,9 +34,10 @@ int round_down_pow2(int x) {
 }
 
 // Launch shape.  The chip holds 1024 SIMDs; a wave streams best when it owns a long run of steps
-// (its start-up and its final store are latency it cannot hide), so:
+// (its start-up and its final store are latency it cannot hide), but ragged batches balance
+// best with many small items, so:
 //   - with plenty of chunks, one-wave workgroups each walk several consecutive chunks
-//     (chunks_per_group, at most 8), stopping at about one wave per SIMD;
+//     (chunks_per_group, at most 4), keeping at least about two waves per SIMD;
 //   - with few (sequence, KV head, chunk) items, the steps of one item are dealt to several waves.
 void pick_shape(int batch, int n_kv_heads, int max_steps, int n_chunks, int *n_waves, int *chunks_per_group) {
     const long items = (long)batch * n_kv_heads * n_chunks;
@@ -48,7 +49,7 @@ void pick_shape(int batch, int n_kv_heads, int max_steps, int n_chunks, int *n_w
     int c = 1;
     if (w == 1 && n_chunks > 1) {
         if (forced_c > 0) c = forced_c;
-        else while (c < 8 && c < n_chunks && items / (2 * c) >= 1024) c *= 2;
+        else while (c < 4 && c < n_chunks && items / (2 * c) >= 2048) c *= 2;
         if (c > n_chunks) c = n_chunks;
     }
     *n_waves = w;

@@ -470,11 +470,11 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             emit_direct(0);
             return;
         }
-        // burst the parked partials out: one 256-byte row per head and chunk, lane = channel;
-        // chunks of the group that lie beyond the context are written as empty partials
+        // burst the parked partials out: 16 lanes cover one 256-byte row, a wave-wide store covers
+        // 4 rows.  Chunks of the group that lie beyond the context were never parked and are not
+        // written: the merge kernel bounds its reads by the sequence length.
         __syncthreads();                               // lanes read what other lanes parked
-        // 16 lanes cover one 256-byte row; a wave-wide store covers 4 rows
-        const int n_rows = (c_last - c_first) * G;
+        const int n_rows = (next_chunk - c_first) * G;
         const int quad = lane & 15;
         for (int r0 = 0; r0 < n_rows; r0 += 16) {
             f32x4 x[4];
@@ -483,7 +483,6 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                 const int r = min(r0 + 4 * u + (lane >> 4), n_rows - 1);
                 const int cl = r / G, h = r - cl * G;
                 x[u] = *reinterpret_cast<const f32x4 *>(&lds[cl * 528 + h * 64 + 4 * quad]);
-                if (c_first + cl >= next_chunk) x[u] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -498,18 +497,18 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         // (m, l) pairs: one lane per (chunk, head)
         for (int r = lane; r < n_rows; r += 64) {
             const int cl = r / G, h = r - cl * G;
-            const bool parked = c_first + cl < next_chunk;
             const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c_first + cl;
             float2 ml;
-            ml.x = parked ? lds[cl * 528 + 512 + h] : -INFINITY;
-            ml.y = parked ? lds[cl * 528 + 520 + h] : 0.f;
+            ml.x = lds[cl * 528 + 512 + h];
+            ml.y = lds[cl * 528 + 520 + h];
             *reinterpret_cast<float2 *>(prm.ws_ml + row * 2) = ml;
         }
         return;
     }
 
-    // n_waves > 1: per-wave result -> LDS (add the two P halves, sum the denominator over the
-    // four lane groups), then merge and write the final row or the sink-free partial
+    // n_waves > 1: per-wave result -> LDS (the two P halves added), then merge and write the final
+    // row or the sink-free partial; a split-K chunk beyond the context is not written at all
+    if (empty && !final_pass) return;
     const float l = add_ror8(st.l[0]);
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -572,8 +571,8 @@ __device__ __forceinline__ float wave_sum(float x) {
 // fetches (m_i, l_i) of chunk i and computes its weight exp(m_i - M); then lane = channel and the
 // 64 accumulator rows are streamed, all 64 loads of a lane in flight together, each row scaled by
 // its chunk's weight read out of the weight register (uniform lane index).  The first batch is
-// fetched before the sequence length is known: every chunk row of the workspace is written by the
-// first pass (empty partials have weight 0), so reading past a short sequence's chunks is safe.
+// fetched before the sequence length is known; rows of chunks beyond the sequence (which the first
+// pass does not write) are inside the workspace, so the read is safe, and they are discarded.
 __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
@@ -594,13 +593,13 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParam
         float x[64];
 #pragma unroll
         for (int u = 0; u < 64; ++u) x[u] = a[(int64_t)min(u, cnt - 1) * 64];
-        if (base == 0 && prm.seq_lens != nullptr) {    // chunks past this bound are empty by construction
+        if (base == 0 && prm.seq_lens != nullptr) {    // chunks past this bound were never written
             const int L = prm.seq_lens[b];
             const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
             const int span = L - (lo & ~63);
             n = min(S, (span + prm.split_tokens - 1) / prm.split_tokens);
         }
-        if (base + lane >= n) v.x = -INFINITY;
+        if (base + lane >= n) v = float2{-INFINITY, 0.f};
         const float M_new = fmaxf(M, wave_max(v.x));
         if (M_new == -INFINITY) continue;              // only empty partials so far, no sink
         const float keep = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((M - M_new) * kLog2e);
@@ -611,7 +610,9 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParam
 #pragma unroll
         for (int u = 0; u < 64; ++u) {
             const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
-            num = __builtin_fmaf(x[u], wu, num);       // rows >= cnt repeat row cnt-1 with weight 0
+            // rows past the sequence's chunks may hold anything (the first batch is fetched before
+            // the bound is known), so they are dropped by a select, not by a zero weight
+            num = __builtin_fmaf(base + u < n ? x[u] : 0.f, wu, num);
         }
     }
     const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
