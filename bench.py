@@ -338,12 +338,80 @@ def run_cfg5(args, pz, wl, torch):
     print(json.dumps(result), flush=True)
 
 
+def run_calib(args, pz, wl, torch):
+    """Max calibration of the KV scales: streaming amax over bf16 K and V (1 Mi tokens x 8 heads x 64
+    channels each, i.e. one cfg3 layer's worth of new K/V), then the two scales."""
+    n = 16 * 65536 * 8 * 64
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    sets = []
+    for _ in range(3):
+        k = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        v = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        for t0 in range(0, n, 1 << 26):
+            m = min(1 << 26, n - t0)
+            k[t0:t0 + m] = torch.randn(m, generator=g, device="cuda").to(torch.bfloat16)
+            v[t0:t0 + m] = torch.randn(m, generator=g, device="cuda").to(torch.bfloat16)
+        sets.append((k, v))
+    amax = torch.zeros(2, dtype=torch.float32, device="cuda")
+    scales = torch.zeros(2, dtype=torch.float32, device="cuda")
+
+    def step(i, ev=None):
+        k, v = sets[i % len(sets)]
+        amax.zero_()
+        if ev is not None:
+            ev[0].record()
+        pz.pz_kv_amax_update(k, v, n, amax)
+        if ev is not None:
+            ev[1].record()
+        pz.pz_kv_scales_from_amax(amax, 1, scales)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    kern = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    nbytes = 2.0 * n * 2
+    result = {"metric": "kv-scale max calibration GB/s (bf16 K and V, 2 x 512 Mi elements)", "value": nbytes / (ms * 1e-3) / 1e9,
+              "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 magnitudes as u16",
+              "data": "synthetic", "config": {"workload": "calib: amax over 2 GiB of bf16 K/V + scales (pow2 round-up)"},
+              "roofline": {"bound": "hbm", "kernel": "kv_amax_kernel", "achieved": nbytes / (kern * 1e-3) / 1e9,
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": nbytes / (kern * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                           "kernel_us_avg": kern * 1e3, "algorithmic_bytes_per_launch": nbytes, "traffic": None}}
+    if args.cpu_seqs > 0:
+        import oracle
+        m = 1 << 24                                               # bounded sample: 16 Mi elements of each tensor
+        kb = sets[0][0][:m].view(torch.int16).cpu().numpy().view(np.uint16)
+        vb = sets[0][1][:m].view(torch.int16).cpu().numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        ak, av = oracle.amax_bf16(kb), oracle.amax_bf16(vb)
+        dt = time.perf_counter() - t0
+        a2 = torch.zeros(2, dtype=torch.float32, device="cuda")
+        pz.pz_kv_amax_update(sets[0][0][:m], sets[0][1][:m], m, a2)
+        got = a2.cpu().numpy()
+        result["cpu_baseline"] = {"value": 2.0 * m * 2 / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": "first 16 Mi elements of K and of V of tensor set 0",
+                                  "parity_exact": bool(got[0] == ak and got[1] == av)}
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS) + ["cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS) + ["cfg5", "calib"])
     ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-bf16", action="store_true", help="skip the BF16-KV comparison run")
     ap.add_argument("--split-tokens", type=int, default=None, help="override the workload's split-K chunk length")
@@ -365,6 +433,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "cfg5":
         return run_cfg5(args, pz, wl, torch)
+    if args.workload == "calib":
+        return run_calib(args, pz, wl, torch)
     spec = dict(WORKLOADS[args.workload])
     if args.split_tokens is not None:
         spec["split_tokens"] = args.split_tokens

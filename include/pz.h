@@ -163,6 +163,24 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
                                        int32_t split_tokens, const float *sinks, float v_scale,
                                        void *out, int32_t out_dtype, void *hip_stream);
 
+/*
+ * Max calibration of the K and V scales of a layer (paper Section 3, "KV Quantization": scales
+ * computed from a dataset by max calibration, then rounded up to a power of two; "all scales are
+ * below 1" on the paper's data, the library does not require it).
+ *
+ * pz_kv_amax_update folds one batch into the running maxima:
+ *     amax[0] = max(amax[0], max_i |k[i]|),   amax[1] = max(amax[1], max_i |v[i]|)
+ *   k, v   : bf16 [n_elems] each (any shape, flattened), 16-byte aligned; NaN elements are ignored
+ *   amax   : device float[2]; the caller sets it to {0, 0} before the first batch
+ * pz_kv_scales_from_amax turns the maxima into scales on the device:
+ *     scales[i] = amax[i] / 448  (one fp32 division);  with round_up_pow2 != 0 then the smallest
+ *     power of two >= that value;  amax[i] == 0 (nothing seen) gives the neutral scale 1
+ *   scales : device float[2] = (k_scale, v_scale); the caller copies them to the host to pass
+ *            them to pz_kv_append_fp8 / pz_decode_attn (scalar arguments)
+ */
+pz_status pz_kv_amax_update(const void *k, const void *v, int64_t n_elems, float *amax, void *hip_stream);
+pz_status pz_kv_scales_from_amax(const float *amax, int32_t round_up_pow2, float *scales, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

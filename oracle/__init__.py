@@ -51,6 +51,10 @@ def lib():
         L.pzo_quantize.argtypes = [C.c_uint16, C.c_float]
         L.pzo_round_scale_up_pow2.restype = C.c_float
         L.pzo_round_scale_up_pow2.argtypes = [C.c_float]
+        L.pzo_amax_bf16.restype = C.c_float
+        L.pzo_amax_bf16.argtypes = [C.c_void_p, C.c_int64]
+        L.pzo_scale_from_amax.restype = C.c_float
+        L.pzo_scale_from_amax.argtypes = [C.c_float, C.c_int]
         L.pzo_kv_append.restype = None
         L.pzo_kv_append.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_float]
@@ -115,6 +119,16 @@ def f32_to_bf16(x) -> np.ndarray:
 
 def round_scale_up_pow2(s: float) -> float:
     return float(lib().pzo_round_scale_up_pow2(float(s)))
+
+
+def amax_bf16(bits) -> float:
+    """Largest magnitude of a bf16 tensor (NaN ignored, empty -> 0)."""
+    x = _req(bits, np.uint16)
+    return float(lib().pzo_amax_bf16(_p(x), x.size))
+
+
+def scale_from_amax(amax: float, round_up_pow2: bool = False) -> float:
+    return float(lib().pzo_scale_from_amax(float(amax), int(bool(round_up_pow2))))
 
 
 # ---------------------------------------------------------------- cache + attention

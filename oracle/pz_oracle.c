@@ -28,6 +28,8 @@
  * reordering: every loop below runs in the order of the definition.  Build with
  * -ffp-contract=off and without fast-math so that each fp32 operation rounds once, as written.
  *
+ * Max calibration of the scales (amax / 448, optional power-of-two round-up) is here as well.
+ *
  * Pins (tests/test_oracle_*.py): E4M3 codec against torch.float8_e4m3fn and a nearest-value
  * search in exact arithmetic; attention against a dense float64 numpy softmax; closed forms for
  * L = 1, q = 0, equal keys; window >= L == full; sink = -inf == plain softmax; chunked partials
@@ -106,6 +108,26 @@ float pzo_round_scale_up_pow2(float s) {
     int ex;
     float f = frexpf(s, &ex);       /* s = f * 2^ex, f in [0.5, 1) */
     return (f == 0.5f) ? s : ldexpf(1.0f, ex);
+}
+
+/* ------------------------------------------------------------------ max calibration */
+
+/* largest magnitude of a bf16 tensor; NaN elements are ignored; an empty tensor gives 0 */
+float pzo_amax_bf16(const uint16_t *x, int64_t n) {
+    float best = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        float a = fabsf(pzo_bf16_to_f32(x[i]));
+        if (a > best) best = a;                 /* false for NaN */
+    }
+    return best;
+}
+
+/* scale of max calibration (paper Section 3, "KV Quantization"): amax / 448, optionally rounded
+ * up to a power of two; amax == 0 (nothing seen) gives the neutral scale 1 */
+float pzo_scale_from_amax(float amax, int round_up_pow2) {
+    float s = amax / 448.0f;
+    if (!(s > 0.0f)) return 1.0f;
+    return round_up_pow2 ? pzo_round_scale_up_pow2(s) : s;
 }
 
 /* ------------------------------------------------------------------ append */

@@ -57,6 +57,10 @@ def lib():
         L.pz_decode_attn_splitk_reduce.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32,
                                                    C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                                    C.c_float, C.c_void_p, C.c_int32, C.c_void_p]
+        L.pz_kv_amax_update.restype = C.c_int
+        L.pz_kv_amax_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        L.pz_kv_scales_from_amax.restype = C.c_int
+        L.pz_kv_scales_from_amax.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -159,4 +163,18 @@ def pz_decode_attn_splitk_reduce(workspace, workspace_bytes, batch, n_q_heads, h
                                             int(out_dtype), _stream(stream))
     if check and st != 0:
         raise PzError(st, "pz_decode_attn_splitk_reduce")
+    return st
+
+
+def pz_kv_amax_update(k, v, n_elems, amax, stream=None, check=True) -> int:
+    st = lib().pz_kv_amax_update(_ptr(k), _ptr(v), int(n_elems), _ptr(amax), _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_kv_amax_update")
+    return st
+
+
+def pz_kv_scales_from_amax(amax, round_up_pow2, scales, stream=None, check=True) -> int:
+    st = lib().pz_kv_scales_from_amax(_ptr(amax), int(bool(round_up_pow2)), _ptr(scales), _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_kv_scales_from_amax")
     return st

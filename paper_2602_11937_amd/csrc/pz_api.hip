@@ -212,4 +212,20 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
 }
 
+pz_status pz_kv_amax_update(const void *k, const void *v, int64_t n_elems, float *amax, void *hip_stream) {
+    if (n_elems < 0) return PZ_ERR_SHAPE;
+    if (n_elems == 0) return PZ_OK;
+    if (k == nullptr || v == nullptr || amax == nullptr) return PZ_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v)) & 15u) return PZ_ERR_UNSUPPORTED;
+    const hipError_t e = pz::launch_kv_amax(static_cast<const uint16_t *>(k), static_cast<const uint16_t *>(v),
+                                            n_elems, amax, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
+pz_status pz_kv_scales_from_amax(const float *amax, int32_t round_up_pow2, float *scales, void *hip_stream) {
+    if (amax == nullptr || scales == nullptr) return PZ_ERR_NULL;
+    const hipError_t e = pz::launch_kv_scales(amax, round_up_pow2 != 0, scales, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
 }  // extern "C"

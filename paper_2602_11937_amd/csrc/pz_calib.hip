@@ -1,0 +1,111 @@
+// Max calibration of the per-layer KV scales for gfx950.
+//
+// Operation (paper Section 3, "KV Quantization"): the K and V scales of a layer come from max
+// calibration over a dataset -- scale = amax / 448 so that the largest magnitude lands on the
+// largest E4M3 value -- and are then rounded up to a power of two.  The dataset is streamed in
+// batches; `amax` (two floats on the device: K, V) carries the running maxima between calls.
+//
+// amax kernel: HBM-bound streaming read of bf16 (2 bytes per element, each read once).  The
+// magnitude of a bf16 value is its low 15 bits, and for non-NaN values the order of those bit
+// patterns is the order of the magnitudes, so the maximum is taken on integers; NaN elements are
+// ignored.  Waves read contiguous 8 KiB tiles, 16 bytes per lane and load; one atomic max per
+// workgroup.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pz_internal.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+__device__ __forceinline__ unsigned mag_max2(unsigned best, unsigned packed) {
+    unsigned lo = packed & 0x7fffu, hi = (packed >> 16) & 0x7fffu;
+    lo = lo > 0x7f80u ? 0u : lo;                       // NaN: ignored
+    hi = hi > 0x7f80u ? 0u : hi;
+    return max(best, max(lo, hi));
+}
+
+__global__ __launch_bounds__(256) void kv_amax_kernel(const uint16_t *__restrict__ k,
+                                                      const uint16_t *__restrict__ v, int64_t n,
+                                                      float *__restrict__ amax) {
+    const uint16_t *x = blockIdx.y == 0 ? k : v;
+    const int64_t n8 = n / 8;
+    const u32x4 *x8 = reinterpret_cast<const u32x4 *>(x);
+    unsigned best = 0;
+    // every wave walks contiguous 8 KiB tiles (8 loads of 1 KiB, all in flight), tiles dealt
+    // round-robin to all waves of the grid
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t n_tiles = n8 / 512;                  // 512 x 16 bytes = 8 KiB
+    for (int64_t t = wave; t < n_tiles; t += n_waves) {
+        const u32x4 *p = x8 + t * 512 + lane;
+        u32x4 a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = p[u * 64];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) best = mag_max2(best, a[u][e]);
+    }
+    for (int64_t i = n_tiles * 512 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8;
+         i += (int64_t)gridDim.x * blockDim.x) {      // what does not fill a tile
+        const u32x4 a = x8[i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) best = mag_max2(best, a[e]);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (unsigned)(n - n8 * 8)) {   // tail elements
+        unsigned m = x[n8 * 8 + threadIdx.x] & 0x7fffu;
+        best = max(best, m > 0x7f80u ? 0u : m);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) best = max(best, (unsigned)__shfl_xor((int)best, d));
+    __shared__ unsigned wave_best[4];
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        best = max(max(wave_best[0], wave_best[1]), max(wave_best[2], wave_best[3]));
+        // fp32 bit patterns of non-negative floats are ordered like the floats themselves
+        atomicMax(reinterpret_cast<unsigned *>(amax) + blockIdx.y, best << 16);
+    }
+}
+
+__global__ void kv_scales_kernel(const float *__restrict__ amax, int round_up_pow2, float *__restrict__ scales) {
+    const int i = threadIdx.x;
+    if (i >= 2) return;
+    float s = __fdiv_rn(amax[i], 448.0f);
+    if (!(s > 0.0f)) {
+        s = 1.0f;                                      // nothing seen (or NaN): the neutral scale
+    } else if (round_up_pow2 && s < INFINITY) {
+        unsigned u = __float_as_uint(s);
+        if (u & 0x007fffffu) {                         // not a power of two already
+            if ((u >> 23) == 0) {                      // subnormal: go through a normal number
+                const float t = s * 0x1p24f;
+                u = (__float_as_uint(t) & 0x7f800000u) + 0x00800000u;
+                s = __uint_as_float(u) * 0x1p-24f;
+            } else {
+                s = __uint_as_float((u & 0x7f800000u) + 0x00800000u);
+            }
+        }
+    }
+    scales[i] = s;
+}
+
+}  // namespace
+
+namespace pz {
+
+hipError_t launch_kv_amax(const uint16_t *k, const uint16_t *v, int64_t n, float *amax, hipStream_t stream) {
+    int64_t blocks = (n / 8 + 256 * 8 - 1) / (256 * 8);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 512) blocks = 512;                    // per tensor: 2 x 512 x 4 waves = 4 per SIMD
+    hipLaunchKernelGGL(kv_amax_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, stream, k, v, n, amax);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_scales(const float *amax, int round_up_pow2, float *scales, hipStream_t stream) {
+    hipLaunchKernelGGL(kv_scales_kernel, dim3(1), dim3(64), 0, stream, amax, round_up_pow2, scales);
+    return hipGetLastError();
+}
+
+}  // namespace pz

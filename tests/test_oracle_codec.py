@@ -187,3 +187,27 @@ def test_round_scale_up_pow2():
     for s in rng.uniform(1e-4, 1.0, 200):
         r = oracle.round_scale_up_pow2(np.float32(s))
         assert r >= np.float32(s) and r < 2 * np.float32(s) and np.log2(r) == int(np.log2(r))
+
+
+def test_max_calibration_amax_and_scale():
+    """amax against numpy's nanmax; the scale is the paper's max calibration (amax lands on 448)."""
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal(10007) * 3).astype(np.float32)
+    x[17] = -41.5
+    x[100] = np.nan
+    bits = bf16_bits(x)
+    bits[100] = 0x7FC1
+    want = np.nanmax(np.abs(bf16_to_f32(bits)))
+    assert oracle.amax_bf16(bits) == want == 41.5
+    assert oracle.amax_bf16(np.zeros(0, dtype=np.uint16)) == 0.0
+    assert oracle.amax_bf16(np.array([0x8000, 0x0000], dtype=np.uint16)) == 0.0
+    s = oracle.scale_from_amax(want)
+    assert s == float(np.float32(want) / np.float32(448))
+    assert int(oracle.quantize(bf16_bits(np.float32([-41.5])), s)[0]) == 0xFE      # amax -> -448
+    assert oracle.scale_from_amax(0.0) == 1.0 and oracle.scale_from_amax(0.0, True) == 1.0
+    p2 = oracle.scale_from_amax(want, True)
+    assert p2 == 0.125 and s <= p2 < 2 * s
+    assert oracle.scale_from_amax(448.0 * 0.25, True) == 0.25                      # already a power of two
+    # a power-of-two scale never overflows what the raw scale did not: |x / p2| <= |x / s| <= 448
+    codes = oracle.quantize(np.delete(bits[:2000], 100), p2)      # without the NaN element
+    assert not np.any((codes & 0x7F) == 0x7F) and (codes & 0x7F).max() <= 0x7E
