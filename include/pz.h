@@ -181,6 +181,44 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
 pz_status pz_kv_amax_update(const void *k, const void *v, int64_t n_elems, float *amax, void *hip_stream);
 pz_status pz_kv_scales_from_amax(const float *amax, int32_t round_up_pow2, float *scales, void *hip_stream);
 
+/*
+ * Host-side page pool of one layer's cache, with page recycling for sliding-window layers (the
+ * per-layer KV footprint of a window layer is bounded by its window, paper Section 2, "Window
+ * attention for long-context inference"; the memory it frees is what lets a single GPU hold a
+ * larger batch).  Pure host code; the pool allocates host memory in create and frees it in destroy.
+ *
+ *   pz_window_pages      most physical pages one sequence of a window layer holds at any time:
+ *                        (window + page_size - 2) / page_size + 1   (0 for window <= 0)
+ *   pz_page_pool_create  num_pages physical pages of page_size positions; block table of
+ *                        [max_seqs][max_pages_per_seq] entries indexed by logical page
+ *                        (position / page_size), all -1; window == 0 = full attention (nothing is
+ *                        recycled before release).  NULL on bad arguments.
+ *   pz_page_pool_append  the next position of sequence `seq` (its current length): first hands
+ *                        back the pages that lie entirely before the window of the grown sequence,
+ *                        then opens a new page if the position starts one.  Returns the slot of
+ *                        the position (>= 0; pass it to pz_kv_append_fp8), or a negative pz_status:
+ *                        PZ_ERR_WORKSPACE when no page is free, PZ_ERR_SHAPE for a bad sequence id
+ *                        or a full block-table row.
+ *   pz_page_pool_release hands back every page of a finished sequence and resets its length.
+ *   pz_page_pool_block_table   host pointer to the table (valid until destroy).
+ *   pz_page_pool_drain_updates copies up to `capacity` pending block-table changes (flat index
+ *                        seq * max_pages_per_seq + logical_page, new value; oldest first) for the
+ *                        caller to mirror into its device table; returns how many were copied.
+ *                        Entries of recycled pages become -1; the attention kernel never uses them.
+ */
+typedef struct pz_page_pool pz_page_pool;
+int32_t pz_window_pages(int32_t window, int32_t page_size);
+pz_page_pool *pz_page_pool_create(int32_t num_pages, int32_t page_size, int32_t max_seqs,
+                                  int32_t max_pages_per_seq, int32_t window);
+void pz_page_pool_destroy(pz_page_pool *pool);
+int64_t pz_page_pool_append(pz_page_pool *pool, int32_t seq);
+pz_status pz_page_pool_release(pz_page_pool *pool, int32_t seq);
+int32_t pz_page_pool_seq_len(const pz_page_pool *pool, int32_t seq);
+int32_t pz_page_pool_free_pages(const pz_page_pool *pool);
+const int32_t *pz_page_pool_block_table(const pz_page_pool *pool);
+int32_t pz_page_pool_drain_updates(pz_page_pool *pool, int32_t *index_out, int32_t *value_out, int32_t capacity);
+int32_t pz_page_pool_pending_updates(const pz_page_pool *pool);
+
 #ifdef __cplusplus
 }
 #endif

@@ -61,6 +61,26 @@ def lib():
         L.pz_kv_amax_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.pz_kv_scales_from_amax.restype = C.c_int
         L.pz_kv_scales_from_amax.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.pz_window_pages.restype = C.c_int32
+        L.pz_window_pages.argtypes = [C.c_int32, C.c_int32]
+        L.pz_page_pool_create.restype = C.c_void_p
+        L.pz_page_pool_create.argtypes = [C.c_int32] * 5
+        L.pz_page_pool_destroy.restype = None
+        L.pz_page_pool_destroy.argtypes = [C.c_void_p]
+        L.pz_page_pool_append.restype = C.c_int64
+        L.pz_page_pool_append.argtypes = [C.c_void_p, C.c_int32]
+        L.pz_page_pool_release.restype = C.c_int
+        L.pz_page_pool_release.argtypes = [C.c_void_p, C.c_int32]
+        L.pz_page_pool_seq_len.restype = C.c_int32
+        L.pz_page_pool_seq_len.argtypes = [C.c_void_p, C.c_int32]
+        L.pz_page_pool_free_pages.restype = C.c_int32
+        L.pz_page_pool_free_pages.argtypes = [C.c_void_p]
+        L.pz_page_pool_block_table.restype = C.POINTER(C.c_int32)
+        L.pz_page_pool_block_table.argtypes = [C.c_void_p]
+        L.pz_page_pool_drain_updates.restype = C.c_int32
+        L.pz_page_pool_drain_updates.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+        L.pz_page_pool_pending_updates.restype = C.c_int32
+        L.pz_page_pool_pending_updates.argtypes = [C.c_void_p]
         _lib = L
     return _lib
 
@@ -178,3 +198,58 @@ def pz_kv_scales_from_amax(amax, round_up_pow2, scales, stream=None, check=True)
     if check and st != 0:
         raise PzError(st, "pz_kv_scales_from_amax")
     return st
+
+
+def pz_window_pages(window, page_size) -> int:
+    return int(lib().pz_window_pages(int(window), int(page_size)))
+
+
+class PagePool:
+    """Thin handle on a pz_page_pool (host-side page allocator with window recycling)."""
+
+    def __init__(self, num_pages, page_size, max_seqs, max_pages_per_seq, window=0):
+        self._h = lib().pz_page_pool_create(int(num_pages), int(page_size), int(max_seqs), int(max_pages_per_seq),
+                                            int(window))
+        if not self._h:
+            raise PzError(-2, "pz_page_pool_create")
+        self.shape = (int(max_seqs), int(max_pages_per_seq))
+
+    def close(self):
+        if self._h:
+            lib().pz_page_pool_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def append(self, seq, check=True) -> int:
+        slot = int(lib().pz_page_pool_append(self._h, int(seq)))
+        if check and slot < 0:
+            raise PzError(slot, "pz_page_pool_append")
+        return slot
+
+    def release(self, seq):
+        st = lib().pz_page_pool_release(self._h, int(seq))
+        if st != 0:
+            raise PzError(st, "pz_page_pool_release")
+
+    def seq_len(self, seq) -> int:
+        return int(lib().pz_page_pool_seq_len(self._h, int(seq)))
+
+    def free_pages(self) -> int:
+        return int(lib().pz_page_pool_free_pages(self._h))
+
+    def block_table(self):
+        """numpy view [max_seqs][max_pages_per_seq] of the pool's host table (valid until close)."""
+        import numpy as np
+        ptr = lib().pz_page_pool_block_table(self._h)
+        return np.ctypeslib.as_array(ptr, shape=self.shape)
+
+    def drain_updates(self):
+        """(flat indices, values) of the block-table entries that changed since the last drain."""
+        import numpy as np
+        n = int(lib().pz_page_pool_pending_updates(self._h))
+        idx = np.empty(n, dtype=np.int32)
+        val = np.empty(n, dtype=np.int32)
+        got = lib().pz_page_pool_drain_updates(self._h, idx.ctypes.data, val.ctypes.data, n) if n else 0
+        assert got == n
+        return idx, val
