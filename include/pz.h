@@ -164,6 +164,42 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
                                        void *out, int32_t out_dtype, void *hip_stream);
 
 /*
+ * Rotary position embedding with YaRN scaling, fused with the quantise-and-append of the new
+ * token (paper Section 2, last paragraph of "Window attention for long-context inference": the
+ * parent's YaRN encoding is kept and its scaling factor raised from 32 to 56).
+ *
+ * pz_rope_yarn_table (host arithmetic, host pointers) fills cos/sin tables [n_pos][head_dim/2]:
+ *   frequency i:  f_i = theta^(-2i/head_dim);  r_i = clamp((i - low) / (high - low), 0, 1) with
+ *   low / high the (fractional) dimensions whose wavelength completes beta_fast / beta_slow
+ *   rotations over original_context positions;  inv_i = f_i (1 - r_i) + (f_i / factor) r_i;
+ *   cos[p][i] = t cos(p inv_i), sin[p][i] = t sin(p inv_i), t = 0.1 ln(factor) + 1 (1 for factor 1).
+ *   factor == 1 is plain rotary embedding.  The parent model's public configuration is theta
+ *   150000, original_context 4096, beta_fast 32, beta_slow 1; the paper's factor is 56.
+ *
+ * pz_rope_kv_append_fp8 (device pointers; cos_tab / sin_tab are device copies of such tables, or of
+ * any other [n_pos][32] tables): for every token t with position p = positions[t] and every head,
+ * channel pairs (i, i+32), c = cos_tab[p][i], s = sin_tab[p][i]:
+ *     o[i] = fma(x[i], c, -(x[i+32] * s)),   o[i+32] = fma(x[i+32], c, x[i] * s)     (fp32)
+ *   q_out[t][h] = bf16(o)  (round to nearest even; q_in == q_out is allowed; n_q_heads == 0 skips q)
+ *   K[slot][g]  = e4m3(o / k_scale) from the fp32 value (bf16 cache: bf16(o));  V as in
+ *   pz_kv_append_fp8 (unrotated).  positions[t] must be < n_pos of the tables (not checked).
+ */
+typedef struct {
+    float theta;
+    float factor;
+    int32_t original_context;
+    float beta_fast;
+    float beta_slow;
+} pz_yarn_params;
+pz_status pz_rope_yarn_table(const pz_yarn_params *prm /* host */, int32_t head_dim, int32_t n_pos,
+                             float *cos_out /* host */, float *sin_out /* host */);
+pz_status pz_rope_kv_append_fp8(const pz_cache *cache /* host */, const void *q_in, void *q_out,
+                                const void *k_new, const void *v_new, const int32_t *positions,
+                                const float *cos_tab, const float *sin_tab, const int64_t *slot_mapping,
+                                int64_t n_tokens, int32_t n_q_heads, float k_scale, float v_scale,
+                                void *hip_stream);
+
+/*
  * Max calibration of the K and V scales of a layer (paper Section 3, "KV Quantization": scales
  * computed from a dataset by max calibration, then rounded up to a power of two; "all scales are
  * below 1" on the paper's data, the library does not require it).

@@ -51,6 +51,13 @@ def lib():
         L.pzo_quantize.argtypes = [C.c_uint16, C.c_float]
         L.pzo_round_scale_up_pow2.restype = C.c_float
         L.pzo_round_scale_up_pow2.argtypes = [C.c_float]
+        L.pzo_yarn_table.restype = None
+        L.pzo_yarn_table.argtypes = [C.c_double, C.c_double, C.c_int, C.c_double, C.c_double, C.c_int, C.c_int,
+                                     C.c_void_p, C.c_void_p]
+        L.pzo_rope_kv_append.restype = None
+        L.pzo_rope_kv_append.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int64, C.c_float, C.c_float]
         L.pzo_amax_bf16.restype = C.c_float
         L.pzo_amax_bf16.argtypes = [C.c_void_p, C.c_int64]
         L.pzo_scale_from_amax.restype = C.c_float
@@ -119,6 +126,33 @@ def f32_to_bf16(x) -> np.ndarray:
 
 def round_scale_up_pow2(s: float) -> float:
     return float(lib().pzo_round_scale_up_pow2(float(s)))
+
+
+def yarn_table(d, n_pos, theta=150000.0, factor=56.0, original_context=4096, beta_fast=32.0, beta_slow=1.0):
+    """(cos, sin) fp32 [n_pos][d/2] of YaRN-scaled rotary embedding, temperature folded in."""
+    cos = np.zeros((n_pos, d // 2), dtype=np.float32)
+    sin = np.zeros((n_pos, d // 2), dtype=np.float32)
+    lib().pzo_yarn_table(float(theta), float(factor), int(original_context), float(beta_fast), float(beta_slow),
+                         int(d), int(n_pos), _p(cos), _p(sin))
+    return cos, sin
+
+
+def rope_kv_append(k_cache, v_cache, q_bits, k_new_bits, v_new_bits, positions, cos_tab, sin_tab, slot_mapping,
+                   k_scale, v_scale) -> np.ndarray:
+    """Fused rotary + append by the definition; returns the rotated q (bf16 bits [T][Hq][d])."""
+    kv_dtype = KV_FP8 if k_cache.dtype == np.uint8 else KV_BF16
+    _, Hkv, d = k_cache.shape
+    q = _req(q_bits, np.uint16)
+    T, Hq, _ = q.shape
+    k_new, v_new = _req(k_new_bits, np.uint16), _req(v_new_bits, np.uint16)
+    pos, slots = _req(positions, np.int32), _req(slot_mapping, np.int64)
+    ct, st = _req(cos_tab, np.float32), _req(sin_tab, np.float32)
+    assert k_new.shape == (T, Hkv, d) and pos.shape == (T,) and slots.shape == (T,)
+    assert ct.shape == st.shape and ct.shape[1] == d // 2 and pos.max(initial=0) < ct.shape[0]
+    q_out = np.zeros_like(q)
+    lib().pzo_rope_kv_append(_p(k_cache), _p(v_cache), kv_dtype, Hkv, Hq, d, _p(q), _p(q_out), _p(k_new), _p(v_new),
+                             _p(pos), _p(ct), _p(st), _p(slots), T, float(k_scale), float(v_scale))
+    return q_out
 
 
 def amax_bf16(bits) -> float:

@@ -110,6 +110,82 @@ float pzo_round_scale_up_pow2(float s) {
     return (f == 0.5f) ? s : ldexpf(1.0f, ex);
 }
 
+/* ------------------------------------------------------------------ rotary embedding (YaRN) */
+
+/* cos/sin tables [n_pos][d/2] of YaRN-scaled rotary embedding (the paper raises the parent's YaRN
+ * factor from 32 to 56, Section 2).  Per frequency pair i: extrapolated frequency f = theta^(-2i/d),
+ * interpolated frequency f / factor; the number of rotations pair i completes over the original
+ * context, rot_i = L0 f / (2 pi), decides the blend: rot_i >= beta_fast keeps f, rot_i <= beta_slow
+ * takes f / factor, in between the blend is linear IN THE DIMENSION INDEX between the two
+ * (fractional) indices where rot equals beta_fast and beta_slow.  cos/sin carry the temperature
+ * 0.1 ln(factor) + 1. */
+void pzo_yarn_table(double theta, double factor, int L0, double beta_fast, double beta_slow, int d,
+                    int n_pos, float *cos_out, float *sin_out) {
+    const double PI = 3.14159265358979323846;
+    int half = d / 2;
+    /* index at which a pair completes `rot` rotations:  L0 theta^(-2i/d) / (2 pi) = rot */
+    double i_fast = -log(beta_fast * 2.0 * PI / L0) / log(theta) * d / 2.0;
+    double i_slow = -log(beta_slow * 2.0 * PI / L0) / log(theta) * d / 2.0;
+    double t = factor > 1.0 ? 1.0 + 0.1 * log(factor) : 1.0;
+    for (int i = 0; i < half; ++i) {
+        double f = exp(-(2.0 * i / d) * log(theta));
+        double w = (i - i_fast) / (i_slow - i_fast);       /* weight of the interpolated frequency */
+        if (w < 0.0) w = 0.0;
+        if (w > 1.0) w = 1.0;
+        double inv = (1.0 - w) * f + w * (f / factor);
+        for (int p = 0; p < n_pos; ++p) {
+            cos_out[(int64_t)p * half + i] = (float)(t * cos(p * inv));
+            sin_out[(int64_t)p * half + i] = (float)(t * sin(p * inv));
+        }
+    }
+}
+
+/* rotate one row of d bf16 channels (pairs (i, i + d/2)) by the table row of its position:
+ *   o[i] = fma(x1, c, -(x2 s)),  o[i + d/2] = fma(x2, c, x1 s)   -- products and fmas round once */
+static void rope_row(const uint16_t *x, const float *c, const float *s, int d, float *o) {
+    int half = d / 2;
+    for (int i = 0; i < half; ++i) {
+        float x1 = pzo_bf16_to_f32(x[i]), x2 = pzo_bf16_to_f32(x[i + half]);
+        float p1 = x2 * s[i], p2 = x1 * s[i];
+        o[i] = fmaf(x1, c[i], -p1);
+        o[i + half] = fmaf(x2, c[i], p2);
+    }
+}
+
+/* fused rotary + append: q_out = bf16(rotated q); K code = e4m3(rotated k / k_scale) from the fp32
+ * value (bf16 cache: bf16(rotated k)); V quantised unrotated.  Oracle cache layout. */
+void pzo_rope_kv_append(void *k_cache, void *v_cache, int kv_dtype, int Hkv, int Hq, int d,
+                        const uint16_t *q_in, uint16_t *q_out, const uint16_t *k_new,
+                        const uint16_t *v_new, const int32_t *positions, const float *cos_tab,
+                        const float *sin_tab, const int64_t *slot_mapping, int64_t T, float k_scale,
+                        float v_scale) {
+    int half = d / 2;
+    float *o = (float *)malloc(sizeof(float) * (size_t)d);
+    for (int64_t t = 0; t < T; ++t) {
+        const float *c = cos_tab + (int64_t)positions[t] * half, *s = sin_tab + (int64_t)positions[t] * half;
+        for (int h = 0; h < Hq; ++h) {
+            rope_row(q_in + (t * Hq + h) * d, c, s, d, o);
+            for (int i = 0; i < d; ++i) q_out[(t * Hq + h) * d + i] = pzo_f32_to_bf16(o[i]);
+        }
+        int64_t slot = slot_mapping[t];
+        if (slot < 0) continue;
+        for (int g = 0; g < Hkv; ++g) {
+            rope_row(k_new + (t * Hkv + g) * d, c, s, d, o);
+            for (int i = 0; i < d; ++i) {
+                int64_t dst = (slot * Hkv + g) * d + i;
+                if (kv_dtype == 0) {
+                    ((uint8_t *)k_cache)[dst] = pzo_e4m3_encode(o[i] / k_scale);
+                    ((uint8_t *)v_cache)[dst] = pzo_quantize(v_new[(t * Hkv + g) * d + i], v_scale);
+                } else {
+                    ((uint16_t *)k_cache)[dst] = pzo_f32_to_bf16(o[i]);
+                    ((uint16_t *)v_cache)[dst] = v_new[(t * Hkv + g) * d + i];
+                }
+            }
+        }
+    }
+    free(o);
+}
+
 /* ------------------------------------------------------------------ max calibration */
 
 /* largest magnitude of a bf16 tensor; NaN elements are ignored; an empty tensor gives 0 */

@@ -23,6 +23,15 @@ class _CCache(C.Structure):
                 ("dtype", C.c_int32)]
 
 
+class YarnParams(C.Structure):
+    """pz_yarn_params; the defaults are the parent model's public configuration with the paper's factor."""
+    _fields_ = [("theta", C.c_float), ("factor", C.c_float), ("original_context", C.c_int32),
+                ("beta_fast", C.c_float), ("beta_slow", C.c_float)]
+
+    def __init__(self, theta=150000.0, factor=56.0, original_context=4096, beta_fast=32.0, beta_slow=1.0):
+        super().__init__(theta, factor, original_context, beta_fast, beta_slow)
+
+
 def lib_path() -> str:
     return os.path.join(_PKG, "libpz.so")
 
@@ -61,6 +70,12 @@ def lib():
         L.pz_kv_amax_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.pz_kv_scales_from_amax.restype = C.c_int
         L.pz_kv_scales_from_amax.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.pz_rope_yarn_table.restype = C.c_int
+        L.pz_rope_yarn_table.argtypes = [C.POINTER(YarnParams), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.pz_rope_kv_append_fp8.restype = C.c_int
+        L.pz_rope_kv_append_fp8.argtypes = [C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                            C.c_float, C.c_float, C.c_void_p]
         L.pz_window_pages.restype = C.c_int32
         L.pz_window_pages.argtypes = [C.c_int32, C.c_int32]
         L.pz_page_pool_create.restype = C.c_void_p
@@ -253,3 +268,24 @@ class PagePool:
         got = lib().pz_page_pool_drain_updates(self._h, idx.ctypes.data, val.ctypes.data, n) if n else 0
         assert got == n
         return idx, val
+
+
+def pz_rope_yarn_table(params, head_dim, n_pos, check=True):
+    """Host tables (cos, sin) as numpy fp32 [n_pos][head_dim/2]."""
+    import numpy as np
+    cos = np.zeros((n_pos, head_dim // 2), dtype=np.float32)
+    sin = np.zeros((n_pos, head_dim // 2), dtype=np.float32)
+    st = lib().pz_rope_yarn_table(C.byref(params), int(head_dim), int(n_pos), cos.ctypes.data, sin.ctypes.data)
+    if check and st != 0:
+        raise PzError(st, "pz_rope_yarn_table")
+    return cos, sin
+
+
+def pz_rope_kv_append_fp8(cache, q_in, q_out, k_new, v_new, positions, cos_tab, sin_tab, slot_mapping, n_tokens,
+                          n_q_heads, k_scale, v_scale, stream=None, check=True) -> int:
+    st = lib().pz_rope_kv_append_fp8(_cache_ref(cache), _ptr(q_in), _ptr(q_out), _ptr(k_new), _ptr(v_new),
+                                     _ptr(positions), _ptr(cos_tab), _ptr(sin_tab), _ptr(slot_mapping), int(n_tokens),
+                                     int(n_q_heads), float(k_scale), float(v_scale), _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_rope_kv_append_fp8")
+    return st

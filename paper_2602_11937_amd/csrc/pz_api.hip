@@ -212,6 +212,71 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
 }
 
+pz_status pz_rope_yarn_table(const pz_yarn_params *prm, int32_t head_dim, int32_t n_pos, float *cos_out,
+                             float *sin_out) {
+    if (prm == nullptr || cos_out == nullptr || sin_out == nullptr) return PZ_ERR_NULL;
+    if (head_dim <= 0 || head_dim % 2 != 0 || n_pos < 0 || prm->original_context <= 0) return PZ_ERR_SHAPE;
+    if (!(prm->theta > 1.0f) || !(prm->factor >= 1.0f) || !(prm->beta_fast > prm->beta_slow) || !(prm->beta_slow > 0.0f))
+        return PZ_ERR_SHAPE;
+    const int half = head_dim / 2;
+    const double two_pi = 6.283185307179586476925286766559;
+    // dimension (fractional) whose wavelength completes `rot` rotations over the original context
+    auto corr_dim = [&](double rot) {
+        return head_dim * log(prm->original_context / (rot * two_pi)) / (2.0 * log((double)prm->theta));
+    };
+    const double low = corr_dim(prm->beta_fast), high = corr_dim(prm->beta_slow);
+    const double temperature = prm->factor > 1.0f ? 0.1 * log((double)prm->factor) + 1.0 : 1.0;
+    for (int i = 0; i < half; ++i) {
+        const double freq = pow((double)prm->theta, -2.0 * i / head_dim);      // extrapolation
+        double ramp = (i - low) / (high - low);
+        ramp = ramp < 0.0 ? 0.0 : (ramp > 1.0 ? 1.0 : ramp);                    // 0: keep, 1: interpolate
+        const double inv = freq * (1.0 - ramp) + (freq / prm->factor) * ramp;
+        for (int p = 0; p < n_pos; ++p) {
+            const double ang = p * inv;
+            cos_out[(size_t)p * half + i] = (float)(cos(ang) * temperature);
+            sin_out[(size_t)p * half + i] = (float)(sin(ang) * temperature);
+        }
+    }
+    return PZ_OK;
+}
+
+pz_status pz_rope_kv_append_fp8(const pz_cache *cache, const void *q_in, void *q_out, const void *k_new,
+                                const void *v_new, const int32_t *positions, const float *cos_tab,
+                                const float *sin_tab, const int64_t *slot_mapping, int64_t n_tokens,
+                                int32_t n_q_heads, float k_scale, float v_scale, void *hip_stream) {
+    const pz_status cs = check_cache(cache);
+    if (cs != PZ_OK) return cs;
+    if (n_tokens < 0 || n_q_heads < 0) return PZ_ERR_SHAPE;
+    if (n_tokens == 0) return PZ_OK;
+    if (k_new == nullptr || v_new == nullptr || slot_mapping == nullptr || positions == nullptr ||
+        cos_tab == nullptr || sin_tab == nullptr)
+        return PZ_ERR_NULL;
+    if (n_q_heads > 0 && (q_in == nullptr || q_out == nullptr)) return PZ_ERR_NULL;
+    if (cache->n_kv_heads + n_q_heads > 65535) return PZ_ERR_UNSUPPORTED;
+    if (cache->dtype == PZ_KV_FP8_E4M3 && (!positive_finite(k_scale) || !positive_finite(v_scale)))
+        return PZ_ERR_SHAPE;
+    pz::RopeAppendParams p;
+    p.ap.k = static_cast<uint8_t *>(cache->k);
+    p.ap.v = static_cast<uint8_t *>(cache->v);
+    p.ap.k_new = static_cast<const uint16_t *>(k_new);
+    p.ap.v_new = static_cast<const uint16_t *>(v_new);
+    p.ap.slot_mapping = slot_mapping;
+    p.ap.T = n_tokens;
+    p.ap.Hkv = cache->n_kv_heads;
+    p.ap.P = cache->page_size;
+    p.ap.k_scale = k_scale;
+    p.ap.v_scale = v_scale;
+    p.q_in = static_cast<const uint16_t *>(q_in);
+    p.q_out = static_cast<uint16_t *>(q_out);
+    p.positions = positions;
+    p.cos_tab = cos_tab;
+    p.sin_tab = sin_tab;
+    p.Hq = n_q_heads;
+    const hipError_t e = pz::launch_rope_kv_append(p, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
+                                                   static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
 pz_status pz_kv_amax_update(const void *k, const void *v, int64_t n_elems, float *amax, void *hip_stream) {
     if (n_elems < 0) return PZ_ERR_SHAPE;
     if (n_elems == 0) return PZ_OK;

@@ -45,6 +45,17 @@ struct AppendParams {
     float k_scale, v_scale;
 };
 
+struct RopeAppendParams {
+    AppendParams ap;             // cache, k_new, v_new, slots, T, scales
+    const uint16_t *q_in;        // bf16 [T][Hq][64]
+    uint16_t *q_out;             // bf16 [T][Hq][64]
+    const int32_t *positions;    // [T]
+    const float *cos_tab;        // [n_pos][32]
+    const float *sin_tab;
+    int32_t Hq;
+};
+
+hipError_t launch_rope_kv_append(const RopeAppendParams &prm, int elem_bytes, hipStream_t stream);
 hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_bytes, int n_waves,
                               hipStream_t stream);
 hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream);
