@@ -164,6 +164,32 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
                                        void *out, int32_t out_dtype, void *hip_stream);
 
 /*
+ * Multi-token (prefill / chunked-prefill) attention over the paged cache: the input half of the
+ * paper's fixed-length serving scenarios (Section 4, 4K/4K and 64K/64K input/output), with the
+ * same per-layer window rule and the same FP8 cache as the decode call.
+ *
+ * The n_b = q_start[b+1] - q_start[b] newest positions of sequence b are queries; their K/V are
+ * already in the cache (append first).  Query i of sequence b sits at position
+ * p = L_b - n_b + i and attends to the positions j in [lo, p], lo = max(0, p - window + 1) for
+ * window > 0, else 0, by the formula of pz_decode_attn with L := p + 1 (sink included).
+ *
+ *   q               : bf16 [T][n_q_heads][head_dim], T = q_start[batch]; the queries of a sequence
+ *                     are contiguous and in position order
+ *   q_start         : int32 [batch + 1], q_start[0] == 0, non-decreasing
+ *   seq_lens        : int32 [batch], L_b counting the new tokens (L_b >= n_b)
+ *   max_new_tokens  : host upper bound of max_b n_b (sizes the launch; a larger value only costs
+ *                     idle workgroups)
+ *   out             : [T][n_q_heads][head_dim], fp32 or bf16
+ * Everything else as in pz_decode_attn.
+ */
+pz_status pz_prefill_attn(const pz_cache *cache /* host */, const void *q, const int32_t *q_start,
+                          const int32_t *block_table, int32_t max_pages_per_seq,
+                          const int32_t *seq_lens, int32_t batch, int32_t n_q_heads,
+                          int32_t max_new_tokens, const float *sinks, float sm_scale, float k_scale,
+                          float v_scale, int32_t window, void *out, int32_t out_dtype,
+                          void *hip_stream);
+
+/*
  * Rotary position embedding with YaRN scaling, fused with the quantise-and-append of the new
  * token (paper Section 2, last paragraph of "Window attention for long-context inference": the
  * parent's YaRN encoding is kept and its scaling factor raised from 32 to 56).

@@ -257,3 +257,26 @@ def splitk_reduce(part_acc, part_ml, sinks, v_scale) -> np.ndarray:
     out = np.zeros((B, Hq, d), dtype=np.float32)
     lib().pzo_splitk_reduce(_p(acc), _p(ml), B, Hq, d, S, _p(sk), float(v_scale), _p(out))
     return out
+
+
+def prefill_attn(k_cache, v_cache, P, q_bits, q_start, block_table, seq_lens, sinks, sm_scale, k_scale, v_scale,
+                 window=0, accum="f32", nthreads=1) -> np.ndarray:
+    """Multi-token attention by the definition: query i of sequence b sits at position
+    p = L_b - n_b + i and is, by definition, a decode query against the first p + 1 positions
+    (causal), inside the window.  So every query token becomes one row of decode_attn with
+    sequence length p + 1 and its sequence's block-table row.  Returns fp32 [T][Hq][d]."""
+    q = _req(q_bits, np.uint16)
+    qs = np.asarray(q_start, dtype=np.int64)
+    bt = _req(block_table, np.int32)
+    sl = np.asarray(seq_lens, dtype=np.int64)
+    T = q.shape[0]
+    assert qs[0] == 0 and qs[-1] == T and len(qs) == len(sl) + 1
+    rows_bt = np.empty((T, bt.shape[1]), dtype=np.int32)
+    rows_len = np.empty(T, dtype=np.int32)
+    for b in range(len(sl)):
+        n = int(qs[b + 1] - qs[b])
+        assert 0 <= n <= sl[b]
+        rows_bt[qs[b]:qs[b + 1]] = bt[b]
+        rows_len[qs[b]:qs[b + 1]] = sl[b] - n + np.arange(n) + 1
+    return decode_attn(k_cache, v_cache, P, q, rows_bt, rows_len, sinks, sm_scale, k_scale, v_scale, window,
+                       accum=accum, nthreads=nthreads)

@@ -70,6 +70,10 @@ def lib():
         L.pz_kv_amax_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.pz_kv_scales_from_amax.restype = C.c_int
         L.pz_kv_scales_from_amax.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.pz_prefill_attn.restype = C.c_int
+        L.pz_prefill_attn.argtypes = [C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_float, C.c_float,
+                                      C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
         L.pz_rope_yarn_table.restype = C.c_int
         L.pz_rope_yarn_table.argtypes = [C.POINTER(YarnParams), C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.pz_rope_kv_append_fp8.restype = C.c_int
@@ -288,4 +292,15 @@ def pz_rope_kv_append_fp8(cache, q_in, q_out, k_new, v_new, positions, cos_tab, 
                                      int(n_q_heads), float(k_scale), float(v_scale), _stream(stream))
     if check and st != 0:
         raise PzError(st, "pz_rope_kv_append_fp8")
+    return st
+
+
+def pz_prefill_attn(cache, q, q_start, block_table, max_pages_per_seq, seq_lens, batch, n_q_heads, max_new_tokens,
+                    sinks, sm_scale, k_scale, v_scale, window, out, out_dtype=OUT_F32, stream=None, check=True) -> int:
+    st = lib().pz_prefill_attn(_cache_ref(cache), _ptr(q), _ptr(q_start), _ptr(block_table), int(max_pages_per_seq),
+                               _ptr(seq_lens), int(batch), int(n_q_heads), int(max_new_tokens), _ptr(sinks),
+                               float(sm_scale), float(k_scale), float(v_scale), int(window), _ptr(out), int(out_dtype),
+                               _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_prefill_attn")
     return st

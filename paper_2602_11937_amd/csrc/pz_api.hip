@@ -212,6 +212,47 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
 }
 
+pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q_start,
+                          const int32_t *block_table, int32_t max_pages_per_seq, const int32_t *seq_lens,
+                          int32_t batch, int32_t n_q_heads, int32_t max_new_tokens, const float *sinks,
+                          float sm_scale, float k_scale, float v_scale, int32_t window, void *out,
+                          int32_t out_dtype, void *hip_stream) {
+    const pz_status cs = check_cache(cache);
+    if (cs != PZ_OK) return cs;
+    if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || max_new_tokens < 0) return PZ_ERR_SHAPE;
+    if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
+    if (n_q_heads / cache->n_kv_heads > 8) return PZ_ERR_UNSUPPORTED;
+    if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
+    if (!positive_finite(sm_scale) || !positive_finite(k_scale) || !positive_finite(v_scale)) return PZ_ERR_SHAPE;
+    if (batch == 0 || max_new_tokens == 0) return PZ_OK;
+    if (q == nullptr || q_start == nullptr || block_table == nullptr || seq_lens == nullptr || out == nullptr)
+        return PZ_ERR_NULL;
+    const int tiles = (max_new_tokens + 2 * PZ_PREFILL_NT - 1) / (2 * PZ_PREFILL_NT);
+    if ((int64_t)batch * tiles * cache->n_kv_heads > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+    pz::PrefillParams p;
+    p.k = static_cast<const uint8_t *>(cache->k);
+    p.v = static_cast<const uint8_t *>(cache->v);
+    p.q = static_cast<const uint16_t *>(q);
+    p.q_start = q_start;
+    p.block_table = block_table;
+    p.seq_lens = seq_lens;
+    p.sinks = sinks;
+    p.out = out;
+    p.max_pages = max_pages_per_seq;
+    p.B = batch;
+    p.Hq = n_q_heads;
+    p.Hkv = cache->n_kv_heads;
+    p.G = n_q_heads / cache->n_kv_heads;
+    p.window = window;
+    p.out_dtype = out_dtype;
+    p.tiles_per_seq = tiles;
+    p.sc = sm_scale * k_scale * 1.4426950408889634f;
+    p.v_scale = v_scale;
+    const hipError_t e = pz::launch_prefill_attn(p, cache->page_size, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2, tiles,
+                                                 static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
 pz_status pz_rope_yarn_table(const pz_yarn_params *prm, int32_t head_dim, int32_t n_pos, float *cos_out,
                              float *sin_out) {
     if (prm == nullptr || cos_out == nullptr || sin_out == nullptr) return PZ_ERR_NULL;

@@ -45,6 +45,24 @@ struct AppendParams {
     float k_scale, v_scale;
 };
 
+#define PZ_PREFILL_NT 2          // column tiles per wave of the prefill kernel: 2 * NT query tokens
+
+struct PrefillParams {
+    const uint8_t *k;
+    const uint8_t *v;
+    const uint16_t *q;           // bf16 [T][Hq][64], the new tokens of a sequence contiguous, in order
+    const int32_t *q_start;      // [B + 1] offsets into T
+    const int32_t *block_table;
+    const int32_t *seq_lens;     // [B], counting the new tokens
+    const float *sinks;
+    void *out;                   // [T][Hq][64]
+    int32_t max_pages, B, Hq, Hkv, G, window, out_dtype, tiles_per_seq;
+    float sc, v_scale;
+};
+
+hipError_t launch_prefill_attn(const PrefillParams &prm, int page_size, int elem_bytes, int n_tiles,
+                               hipStream_t stream);
+
 struct RopeAppendParams {
     AppendParams ap;             // cache, k_new, v_new, slots, T, scales
     const uint16_t *q_in;        // bf16 [T][Hq][64]

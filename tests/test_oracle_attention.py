@@ -318,3 +318,41 @@ def test_reduce_closed_forms():
     acc3[:] = 0
     assert np.all(oracle.splitk_reduce(acc3, ml3, None, 1.0) == 0)
     assert np.all(oracle.splitk_reduce(acc3, ml3, sinks, 1.0) == 0)
+
+
+# ---------------------------------------------------------------- multi-token (prefill) definition
+
+def test_prefill_is_causal_attention_inside_the_window():
+    """Dense float64 check of the multi-token definition: token i of the n newest sees positions
+    up to its own and no more than the window before it."""
+    case = small_case(seed=30, seq_lens=[90, 37, 16], P=16)
+    kc, vc = oracle_cache(case)
+    n_new = [40, 37, 3]
+    q_start = np.concatenate([[0], np.cumsum(n_new)])
+    rng = np.random.default_rng(30)
+    q = wl.bf16_bits(rng.standard_normal((q_start[-1], case.Hq, case.d)).astype(np.float32))
+    G = case.Hq // case.Hkv
+    for window in (0, 25):
+        got = oracle.prefill_attn(kc, vc, case.P, q, q_start, case.block_table, case.seq_lens, case.sinks,
+                                  case.sm_scale, case.k_scale, case.v_scale, window, accum="f64")
+        qf = wl.bf16_to_f32(q).astype(np.float64)
+        want = np.zeros_like(got, dtype=np.float64)
+        off = case.offsets
+        for b in range(case.B):
+            L = int(case.seq_lens[b])
+            slots = case.slot_mapping[off[b]:off[b + 1]]
+            for i in range(n_new[b]):
+                p = L - n_new[b] + i
+                lo = max(0, p - window + 1) if window else 0
+                for h in range(case.Hq):
+                    K = torch_decode_e4m3(kc[slots[lo:p + 1], h // G]) * case.k_scale
+                    V = torch_decode_e4m3(vc[slots[lo:p + 1], h // G]) * case.v_scale
+                    s = case.sm_scale * (K @ qf[q_start[b] + i, h])
+                    mx = max(s.max(), float(case.sinks[h]))
+                    w = np.exp(s - mx)
+                    want[q_start[b] + i, h] = (w @ V) / (w.sum() + np.exp(float(case.sinks[h]) - mx))
+        assert rel_err(got, want) < 1e-6
+    # one new token per sequence is the decode call
+    one = oracle.prefill_attn(kc, vc, case.P, case.q, np.arange(case.B + 1), case.block_table, case.seq_lens,
+                              case.sinks, case.sm_scale, case.k_scale, case.v_scale, 0)
+    assert np.array_equal(one, run(case, kc, vc))
