@@ -406,12 +406,86 @@ def run_calib(args, pz, wl, torch):
     print(json.dumps(result), flush=True)
 
 
+def run_prefill(args, pz, wl, torch):
+    """Chunked prefill: batch 8, context 32768, the last 2048 positions of every sequence are queries
+    (full attention and window 8192).  Matrix-core bound: 4 * d flop per (query, head, attended position)."""
+    B, L, n_new = 8, 32768, 2048
+    spec = dict(B=B, L=L, window=0, split_tokens=0, outlier_frac=0.0, seed=6)
+    layer = Layer(pz, wl, torch, spec, seed=6, kv_dtype=pz.KV_FP8, keep_context=args.cpu_seqs > 0)
+    lay = layer.lay
+    g = torch.Generator(device="cuda")
+    g.manual_seed(66)
+    q = torch.randn((B * n_new, lay.Hq, lay.d), generator=g, device="cuda").to(torch.bfloat16)
+    q_start = torch.arange(0, (B + 1) * n_new, n_new, dtype=torch.int32, device="cuda")
+    out = torch.empty((B * n_new, lay.Hq, lay.d), dtype=torch.float32, device="cuda")
+    results = {}
+    for window in (0, 8192):
+        def call():
+            pz.pz_prefill_attn(layer.cache, q, q_start, lay.block_table, layer.max_pages, lay.seq_lens_dev, B, lay.Hq,
+                               n_new, lay.sinks, lay.sm_scale, layer.k_scale, layer.v_scale, window, out)
+        for _ in range(max(1, args.warmup // 4)):
+            call()
+        steps = max(3, args.steps // 20)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for a, b_ in evs:
+            a.record(); call(); b_.record()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        kern = float(np.mean([a.elapsed_time(b_) for a, b_ in evs]))
+        pos = L - n_new + np.arange(n_new, dtype=np.int64)
+        n_att = (np.minimum(pos + 1, window) if window else pos + 1).sum()
+        flops = 4.0 * lay.d * lay.Hq * B * float(n_att)
+        results[window] = dict(ms=ms, kern_ms=kern, tflops=flops / (kern * 1e-3) / 1e12, flops=flops,
+                               tokens_per_s=B * n_new / (ms * 1e-3))
+    r0 = results[0]
+    result = {"metric": "prefill-attention TFLOP/s + prompt tokens/s, batch 8 x 2048 new tokens at context 32768, FP8 KV",
+              "value": r0["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": max(3, args.steps // 20),
+              "warmup": max(1, args.warmup // 4), "ms_per_step": r0["ms"], "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "e4m3 KV -> bf16 MFMA operands, f32 accumulate", "data": "synthetic",
+              "config": {"workload": "prefill: batch 8, context 32768, last 2048 positions are queries, 64 q / 8 KV heads, "
+                                     "d=64, paged E4M3 KV, causal + sinks (also window 8192)"},
+              "prompt_tokens_per_s": r0["tokens_per_s"],
+              "roofline": {"bound": "mfma", "kernel": "prefill_attn_kernel<64,1,%d>" % 2, "achieved": r0["tflops"],
+                           "peak": 2500.0, "unit": "TFLOP/s", "frac": r0["tflops"] / 2500.0,
+                           "kernel_us_avg": r0["kern_ms"] * 1e3, "algorithmic_flops_per_launch": r0["flops"],
+                           "traffic": None},
+              "window_8192": {"ms_per_step": results[8192]["ms"], "TFLOPs": results[8192]["tflops"],
+                              "prompt_tokens_per_s": results[8192]["tokens_per_s"]}}
+    if args.cpu_seqs > 0:
+        import oracle
+        kc, vc, bt, _, new_k, new_v, new_slots = oracle_sample(oracle, torch, layer, [0])
+        oracle.kv_append(kc, vc, new_k, new_v, new_slots, lay.k_scale, lay.v_scale)
+        n_s = 32                                                   # bounded sample: the last 32 queries of sequence 0
+        qs = q[n_new - n_s:n_new].view(torch.int16).cpu().numpy().view(np.uint16)
+        cores = min(len(os.sched_getaffinity(0)), 16)
+        call_window = 0
+        pz.pz_prefill_attn(layer.cache, q, q_start, lay.block_table, layer.max_pages, lay.seq_lens_dev, B, lay.Hq, n_new,
+                           lay.sinks, lay.sm_scale, layer.k_scale, layer.v_scale, call_window, out)
+        torch.cuda.synchronize()
+        got = out[n_new - n_s:n_new].cpu().numpy()
+        t0 = time.perf_counter()
+        # the sample as a chunk of its own: the n_s newest positions of sequence 0
+        want = oracle.prefill_attn(kc, vc, lay.P, qs, np.array([0, n_s]), bt, lay.seq_lens[:1], lay.sinks.cpu().numpy(),
+                                   lay.sm_scale, lay.k_scale, lay.v_scale, call_window, nthreads=cores)
+        dt = time.perf_counter() - t0
+        fl = 4.0 * lay.d * lay.Hq * float((L - n_s + np.arange(n_s) + 1).sum())
+        rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
+        result["cpu_baseline"] = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+                                  "sample": "the last %d query positions of sequence 0 (all 64 heads, full attention)" % n_s,
+                                  "parity_max_abs_over_rms": float(np.max(np.abs(got - want)) / rms)}
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS) + ["cfg5", "calib"])
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS) + ["cfg5", "calib", "prefill"])
     ap.add_argument("--cpu-seqs", type=int, default=4, help="sequences in the oracle's bounded sample (0 = skip)")
     ap.add_argument("--no-bf16", action="store_true", help="skip the BF16-KV comparison run")
     ap.add_argument("--split-tokens", type=int, default=None, help="override the workload's split-K chunk length")
@@ -435,6 +509,8 @@ def main():
         return run_cfg5(args, pz, wl, torch)
     if args.workload == "calib":
         return run_calib(args, pz, wl, torch)
+    if args.workload == "prefill":
+        return run_prefill(args, pz, wl, torch)
     spec = dict(WORKLOADS[args.workload])
     if args.split_tokens is not None:
         spec["split_tokens"] = args.split_tokens
