@@ -104,3 +104,38 @@ def test_error_wrapper_raises():
     with pytest.raises(pz.PzError) as e:
         pz.pz_decode_attn(cache(head_dim=128), 1, 1, 1, 1, 1, 8, None, 1, 1, 1, 0, 0, 0, None, 0, 1, stream=0)
     assert e.value.status == -3
+
+
+def test_new_entry_points_reject_bad_arguments():
+    lib = pz.lib()
+    c = cache()
+    # calibration
+    assert pz.pz_kv_amax_update(None, 0x10, 8, 0x20, stream=0, check=False) == -1
+    assert pz.pz_kv_amax_update(0x10, 0x20, -1, 0x30, stream=0, check=False) == -2
+    assert pz.pz_kv_amax_update(0x11, 0x20, 8, 0x30, stream=0, check=False) == -3      # unaligned
+    assert pz.pz_kv_amax_update(0x10, 0x20, 0, None, stream=0, check=False) == 0
+    assert pz.pz_kv_scales_from_amax(None, 1, 0x10, stream=0, check=False) == -1
+    # rotary + append
+    def rope(cc, **kw):
+        a = dict(q_in=0x10, q_out=0x10, k=0x20, v=0x30, pos=0x40, cos=0x50, sin=0x60, slots=0x70, n=4, hq=64, ks=0.01, vs=0.01)
+        a.update(kw)
+        return pz.pz_rope_kv_append_fp8(cc, a["q_in"], a["q_out"], a["k"], a["v"], a["pos"], a["cos"], a["sin"],
+                                        a["slots"], a["n"], a["hq"], a["ks"], a["vs"], stream=0, check=False)
+    assert rope(None) == -1 and rope(c, pos=None) == -1 and rope(c, cos=None) == -1 and rope(c, q_out=None) == -1
+    assert rope(c, n=-1) == -2 and rope(c, ks=0.0) == -2 and rope(c, n=0) == 0
+    assert rope(cache(head_dim=128)) == -3
+    # prefill
+    def pre(cc, **kw):
+        a = dict(q=0x10, qs=0x20, bt=0x30, mp=4, sl=0x40, b=2, hq=64, mx=16, sinks=None, sm=0.125, ks=0.01, vs=0.01,
+                 w=0, out=0x50, odt=0)
+        a.update(kw)
+        return pz.pz_prefill_attn(cc, a["q"], a["qs"], a["bt"], a["mp"], a["sl"], a["b"], a["hq"], a["mx"], a["sinks"],
+                                  a["sm"], a["ks"], a["vs"], a["w"], a["out"], a["odt"], stream=0, check=False)
+    assert pre(None) == -1 and pre(c, qs=None) == -1 and pre(c, out=None) == -1
+    assert pre(c, hq=60) == -2 and pre(c, mx=-1) == -2 and pre(c, sm=0.0) == -2
+    assert pre(cache(n_kv_heads=2)) == -3 and pre(c, odt=5) == -3
+    assert pre(c, b=0) == 0 and pre(c, mx=0) == 0
+    # page pool
+    assert lib.pz_page_pool_create(4, 16, 1, 0, 0) is None
+    assert lib.pz_page_pool_append(None, 0) == -1 and lib.pz_page_pool_free_pages(None) == -1
+    assert pz.pz_window_pages(-3, 16) == 0
