@@ -133,8 +133,11 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     const int n_waves = blockDim.x >> 6;
     const bool direct = n_waves == 1;
     const bool final_pass = prm.split_tokens == 0;
-    const int bg = blockIdx.x % (prm.B * prm.Hkv);     // group-major block order
-    const int cgrp = blockIdx.x / (prm.B * prm.Hkv);
+    // group-major block order, LAST chunk group first: in a ragged batch the high groups exist only
+    // for the longest sequences, and dispatching them first leaves the dense low groups -- work for
+    // every CU -- for the end of the kernel instead of a thin tail of a few long sequences
+    const int bg = blockIdx.x % (prm.B * prm.Hkv);
+    const int cgrp = (int)(gridDim.x / (prm.B * prm.Hkv)) - 1 - (int)(blockIdx.x / (prm.B * prm.Hkv));
     const int b = bg / prm.Hkv, g = bg % prm.Hkv;
     const int G = prm.G;
     const int n = lane & 15, kb = lane >> 4;
