@@ -9,7 +9,11 @@ windows), all through the C ABI.  Inputs are seeded synthetic gpt-oss-shaped ten
 in HBM before the timed region.  Consecutive steps walk over several independent cache
 instances so that no step re-reads data the 256 MB Infinity Cache may still hold.
 
-Prints ONE JSON line (see the design doc for the field definitions).
+Prints ONE JSON line: metric / value (algorithmic GB/s of the whole step) / ms_per_step, `roofline`
+(the dominant kernel: algorithmic bytes per launch over its event-timed duration, against the 8 TB/s
+HBM peak, plus the HBM traffic measured with hardware counters), `cpu_baseline` (the CPU oracle timed
+on a bounded sample of the same workload, with a parity figure), `bf16_kv` (the same step on a BF16
+cache) and `tuned_split` (the same step with longer split-K chunks).
 """
 from __future__ import annotations
 
@@ -493,7 +497,7 @@ def main():
                     help="also run one plain 768 MiB device-to-device copy (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build is single-GPU (the path needs no collective; see DESIGN.md on sharding): "
+        print("bench.py: this build is single-GPU (the decode-attention path needs no collective: it shards over KV heads or sequences): "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -1,6 +1,6 @@
 """Full-size parity on sampled sequences, in the launch configuration bench.py times.
 
-The configurations are BASELINE.json's (gpt-oss head geometry, page 64): the inputs are drawn on
+The configurations are the benchmark's (gpt-oss head geometry, page 64): the inputs are drawn on
 the device by workloads.device_layer, the cache is built by pz_kv_append_fp8, and the oracle
 recomputes a few whole sequences from the same bf16 K/V (its own quantisation, its own layout)."""
 import numpy as np
