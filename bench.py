@@ -182,6 +182,32 @@ def time_steps(torch, layers, steps, warmup, events):
     return (t1 - t0) * 1e3 / steps, kern_ms
 
 
+def capture(torch, fn):
+    """Record fn's launches (kernels only: the library enqueues nothing else) into a HIP graph."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    return graph
+
+
+def time_graphs(torch, graphs, steps, warmup):
+    """The same K timed steps, each step one replay of a pre-recorded HIP graph."""
+    for i in range(warmup):
+        graphs[i % len(graphs)].replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        graphs[(warmup + i) % len(graphs)].replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def oracle_sample(oracle, torch, layer, seqs):
     """Oracle-side copy of the listed sequences of a Layer: its own cache (compact page numbering,
     its own layout) filled by the oracle's quantise-and-append from the same bf16 K/V, all but the
@@ -308,6 +334,12 @@ def run_cfg5(args, pz, wl, torch):
                      "frac": full_bytes / (kern_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, "kernel_us_avg": kern_avg * 1e3,
                      "ms_per_step_with_events": ms_ev, "algorithmic_bytes_per_launch": full_bytes, "traffic": None},
     }
+    graph = capture(torch, model.step)                            # all 90 launches of the step in one HIP graph
+    ms_g = time_graphs(torch, [graph], args.steps, args.warmup)
+    result["hip_graph"] = {"ms_per_step": ms_g, "GBps": step_bytes / (ms_g * 1e-3) / 1e9,
+                           "pct_hbm_peak": 100.0 * step_bytes / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                           "attn_tokens_per_s": B / (ms_g * 1e-3)}
+    del graph
     if args.cpu_seqs > 0:
         import oracle
         n_seq = min(args.cpu_seqs, B)
@@ -557,6 +589,12 @@ def main():
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.split_tokens is None else None},
     }
+    # the same step launched as one replay of a recorded HIP graph (one graph per cache instance)
+    graphs = [capture(torch, l.step) for l in layers]
+    ms_g = time_graphs(torch, graphs, args.steps, args.warmup)
+    result["hip_graph"] = {"ms_per_step": ms_g, "GBps": step_bytes / (ms_g * 1e-3) / 1e9,
+                           "pct_hbm_peak": 100.0 * step_bytes / (ms_g * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    del graphs
     if args.workload == "cfg3" and args.split_tokens is None:
         # the same step with the chunk length a caller free to choose would use (fewer, longer partials)
         for l in layers:

@@ -20,7 +20,8 @@
  *     PZ_ERR_LAUNCH.  Out-of-range block-table entries or slots are the caller's bug and are
  *     not detected.
  *   - Supported shapes: head_dim == 64; page_size in {16, 32, 64}; n_q_heads a multiple of
- *     n_kv_heads with group size n_q_heads / n_kv_heads <= 8.
+ *     n_kv_heads with group size n_q_heads / n_kv_heads <= 8, or an even group size <= 16
+ *     (the attention kernels then read each KV head twice, once per half of its group).
  *
  * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
  * discuss paging):

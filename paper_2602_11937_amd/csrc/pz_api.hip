@@ -20,6 +20,11 @@ pz_status check_cache(const pz_cache *c) {
 
 bool positive_finite(float x) { return x > 0.0f && isfinite(x); }
 
+// Query heads per KV head the attention kernels take: a column tile holds 8 heads, so up to 8
+// directly; an even group of up to 16 runs as two virtual KV heads of half the group each, both
+// reading the same cache head.
+bool group_supported(int group) { return group >= 1 && (group <= 8 || (group <= 16 && group % 2 == 0)); }
+
 int env_int(const char *name, int fallback) {
     const char *s = getenv(name);
     if (s == nullptr || *s == 0) return fallback;
@@ -124,7 +129,7 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || split_tokens < 0)
         return PZ_ERR_SHAPE;
     if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
-    if (n_q_heads / cache->n_kv_heads > 8) return PZ_ERR_UNSUPPORTED;
+    if (!group_supported(n_q_heads / cache->n_kv_heads)) return PZ_ERR_UNSUPPORTED;
     if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
     if (!positive_finite(sm_scale) || !positive_finite(k_scale) || !positive_finite(v_scale))
         return PZ_ERR_SHAPE;
@@ -140,7 +145,7 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
         return PZ_ERR_NULL;
     }
     const int n_chunks = split_tokens > 0 ? n_splits : 1;
-    if ((int64_t)batch * cache->n_kv_heads * n_chunks > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+    if ((int64_t)batch * cache->n_kv_heads * 2 * n_chunks > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
 
     pz::AttnParams p;
     p.k = static_cast<const uint8_t *>(cache->k);
@@ -157,8 +162,10 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     p.max_pages = max_pages_per_seq;
     p.B = batch;
     p.Hq = n_q_heads;
-    p.Hkv = cache->n_kv_heads;
-    p.G = n_q_heads / cache->n_kv_heads;
+    p.cache_heads = cache->n_kv_heads;
+    p.head_shift = n_q_heads / cache->n_kv_heads > 8 ? 1 : 0;
+    p.Hkv = cache->n_kv_heads << p.head_shift;
+    p.G = n_q_heads / p.Hkv;
     p.window = window;
     p.split_tokens = split_tokens;
     p.n_splits = split_tokens > 0 ? n_splits : 1;
@@ -172,7 +179,7 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     if (split_tokens > 0 && split_tokens < max_tokens) max_tokens = split_tokens;
     const int max_steps = (int)((max_tokens + 63) / 64);
     int n_waves = 1, chunks_per_group = 1;
-    pick_shape(batch, cache->n_kv_heads, max_steps, n_chunks, &n_waves, &chunks_per_group);
+    pick_shape(batch, p.Hkv, max_steps, n_chunks, &n_waves, &chunks_per_group);
     p.chunks_per_group = chunks_per_group;
     const hipError_t e = pz::launch_decode_attn(p, cache->page_size, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
                                                 n_waves, static_cast<hipStream_t>(hip_stream));
@@ -221,14 +228,14 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     if (cs != PZ_OK) return cs;
     if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || max_new_tokens < 0) return PZ_ERR_SHAPE;
     if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
-    if (n_q_heads / cache->n_kv_heads > 8) return PZ_ERR_UNSUPPORTED;
+    if (!group_supported(n_q_heads / cache->n_kv_heads)) return PZ_ERR_UNSUPPORTED;
     if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
     if (!positive_finite(sm_scale) || !positive_finite(k_scale) || !positive_finite(v_scale)) return PZ_ERR_SHAPE;
     if (batch == 0 || max_new_tokens == 0) return PZ_OK;
     if (q == nullptr || q_start == nullptr || block_table == nullptr || seq_lens == nullptr || out == nullptr)
         return PZ_ERR_NULL;
     const int tiles = (max_new_tokens + 2 * PZ_PREFILL_NT - 1) / (2 * PZ_PREFILL_NT);
-    if ((int64_t)batch * tiles * cache->n_kv_heads > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+    if ((int64_t)batch * tiles * cache->n_kv_heads * 2 > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
     pz::PrefillParams p;
     p.k = static_cast<const uint8_t *>(cache->k);
     p.v = static_cast<const uint8_t *>(cache->v);
@@ -241,8 +248,10 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     p.max_pages = max_pages_per_seq;
     p.B = batch;
     p.Hq = n_q_heads;
-    p.Hkv = cache->n_kv_heads;
-    p.G = n_q_heads / cache->n_kv_heads;
+    p.cache_heads = cache->n_kv_heads;
+    p.head_shift = n_q_heads / cache->n_kv_heads > 8 ? 1 : 0;
+    p.Hkv = cache->n_kv_heads << p.head_shift;
+    p.G = n_q_heads / p.Hkv;
     p.window = window;
     p.out_dtype = out_dtype;
     p.tiles_per_seq = tiles;

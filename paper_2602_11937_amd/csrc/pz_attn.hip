@@ -238,9 +238,9 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             }
             const unsigned lo_mask = (n >= 8) ? 0xffff0000u : 0u;
             const LaneGeom geom = lane_geom<P, EB>(lane);
-            const int64_t page_bytes = (int64_t)prm.Hkv * P * 64 * EB;
-            const uint8_t *kbase = prm.k + (int64_t)g * P * 64 * EB;
-            const uint8_t *vbase = prm.v + (int64_t)g * P * 64 * EB;
+            const int64_t page_bytes = (int64_t)prm.cache_heads * P * 64 * EB;
+            const uint8_t *kbase = prm.k + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
+            const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
             const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
             const float sc = prm.sc;
             const int steps_per_chunk = prm.split_tokens >> 6;

@@ -17,7 +17,8 @@ struct AttnParams {
     float *ws_acc;               // split-K partials [B][Hq][S][64]
     float *ws_ml;                // [B][Hq][S][2]
     void *out;                   // [B][Hq][64]
-    int32_t max_pages, B, Hq, Hkv, G;
+    int32_t max_pages, B, Hq, Hkv, G;   // Hkv, G: "virtual" KV heads of at most 8 query heads each
+    int32_t cache_heads, head_shift;    // KV heads of the cache; virtual head g reads cache head g >> head_shift
     int32_t window, split_tokens, n_splits, out_dtype;
     int32_t chunks_per_group;    // consecutive split-K chunks walked by one workgroup (1 unless it is one wave)
     float sc;                    // sm_scale * k_scale * log2(e)
@@ -56,7 +57,8 @@ struct PrefillParams {
     const int32_t *seq_lens;     // [B], counting the new tokens
     const float *sinks;
     void *out;                   // [T][Hq][64]
-    int32_t max_pages, B, Hq, Hkv, G, window, out_dtype, tiles_per_seq;
+    int32_t max_pages, B, Hq, Hkv, G, window, out_dtype, tiles_per_seq;   // Hkv, G: virtual heads as in AttnParams
+    int32_t cache_heads, head_shift;
     float sc, v_scale;
 };
 

@@ -73,9 +73,9 @@ __global__ __launch_bounds__(64) void prefill_attn_kernel(const pz::PrefillParam
     }
 
     const LaneGeom geom = lane_geom<P, EB>(lane);
-    const int64_t page_bytes = (int64_t)prm.Hkv * P * 64 * EB;
-    const uint8_t *kbase = prm.k + (int64_t)g * P * 64 * EB;
-    const uint8_t *vbase = prm.v + (int64_t)g * P * 64 * EB;
+    const int64_t page_bytes = (int64_t)prm.cache_heads * P * 64 * EB;
+    const uint8_t *kbase = prm.k + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
+    const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
     const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
     const int pmin = j_begin / P, pmax = (j_end - 1) / P;
     const float sc = prm.sc;

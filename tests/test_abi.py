@@ -64,6 +64,8 @@ def test_decode_attn_rejects_bad_arguments_before_any_launch():
     assert attn(cache(dtype=7)) == UNSUP
     assert attn(cache(), n_q_heads=60) == SHAPE                      # not a multiple of the KV heads
     assert attn(cache(n_kv_heads=2), n_q_heads=64) == UNSUP          # group of 32
+    assert attn(cache(n_kv_heads=2), n_q_heads=18) == UNSUP          # odd group above 8
+    assert attn(cache(n_kv_heads=2), n_q_heads=32, batch=0) == 0     # even group of 16 is taken
     assert attn(cache(), batch=-1) == SHAPE and attn(cache(), window=-5) == SHAPE
     assert attn(cache(), sm_scale=0.0) == SHAPE and attn(cache(), k_scale=-1.0) == SHAPE
     assert attn(cache(), v_scale=float("nan")) == SHAPE
