@@ -589,6 +589,25 @@ def main():
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.split_tokens is None else None},
     }
+    # the box's plain streaming-read rate over the very same cache bytes: the library's amax kernel
+    # (16-byte loads, a max per element, nothing written) run over the K and V arrays of each instance
+    if args.workload in ("cfg3", "cfg2"):
+        amax = torch.zeros(2, dtype=torch.float32, device="cuda")
+        n_el = layers[0].cache.k.numel() // 2
+        for l in layers:
+            pz.pz_kv_amax_update(l.cache.k, l.cache.v, n_el, amax)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for i, (a, b) in enumerate(evs):
+            l = layers[i % len(layers)]
+            a.record()
+            pz.pz_kv_amax_update(l.cache.k, l.cache.v, n_el, amax)
+            b.record()
+        torch.cuda.synchronize()
+        ms_r = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        rd = 2.0 * layers[0].cache.k.numel() / (ms_r * 1e-3) / 1e9
+        result["stream_read"] = {"GBps": rd, "pct_hbm_peak": 100.0 * rd / HBM_PEAK_GBPS, "kernel": "kv_amax_kernel over "
+                                 "the K and V arrays of the same cache instances (sequential addresses)",
+                                 "attn_kernel_pct_of_it": 100.0 * result["roofline"]["achieved"] / rd}
     # the same step launched as one replay of a recorded HIP graph (one graph per cache instance)
     graphs = [capture(torch, l.step) for l in layers]
     ms_g = time_graphs(torch, graphs, args.steps, args.warmup)
