@@ -78,9 +78,6 @@ class Layer:
         B = spec["B"]
         if isinstance(spec["L"], tuple):
             seq_lens = wl.ragged_lengths(spec["seed"], B, *spec["L"])
-            if os.environ.get("PZ_BENCH_ROUND_LENS"):             # diagnostic: round the ragged lengths up
-                r = int(os.environ["PZ_BENCH_ROUND_LENS"])
-                seq_lens = ((seq_lens + r - 1) // r * r).astype(np.int32)
         else:
             seq_lens = np.full(B, spec["L"], dtype=np.int32)
         self.pz, self.torch = pz, torch
@@ -114,8 +111,6 @@ class Layer:
         pz, lay = self.pz, self.lay
         self.split = split_tokens
         self.S = pz.pz_decode_attn_n_splits(int(lay.seq_lens.max()), self.window, self.split) if self.split else 0
-        if self.split and os.environ.get("PZ_BENCH_EXTRA_SPLITS"):   # diagnostic: surplus (empty) chunks
-            self.S += int(os.environ["PZ_BENCH_EXTRA_SPLITS"])
         self.ws_bytes = pz.pz_decode_attn_workspace_bytes(lay.B, lay.Hq, lay.d, self.S) if self.split else 0
         self.ws = self.torch.empty((max(self.ws_bytes, 4) // 4,), dtype=self.torch.float32, device="cuda")
 

@@ -42,18 +42,12 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 // Reductions over the four 16-lane rows of a wave (lanes n, n+16, n+32, n+48) without LDS:
 // v_permlane16_swap(x, x) yields (rows 0,0,2,2 | rows 1,1,3,3) and v_permlane32_swap(y, y)
-// yields (low half twice | high half twice), so two swaps and two ops reduce over the rows.
+// yields (low half twice | high half twice), so two swaps and two max operations reduce over the rows.
 __device__ __forceinline__ float rows_max(float x) {
     u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
     u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
     return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
-}
-__device__ __forceinline__ float rows_sum(float x) {
-    u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-    u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
-    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 __device__ __forceinline__ float bf16_round_to_f32bits(float x, uint16_t *bits) {
