@@ -61,3 +61,16 @@ def rel_err(got, want):
     want = np.asarray(want, dtype=np.float64)
     rms = np.sqrt(np.mean(want ** 2))
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - want)) / (rms if rms > 0 else 1.0))
+
+
+def paper_values():
+    """The values the paper prints (tests/golden/paper_values.txt) as a dict of floats."""
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.txt")) as f:
+        for line in f:
+            line = line.split("#", 1)[0].strip()
+            if line:
+                key, val = (x.strip() for x in line.split("=", 1))
+                out[key] = float(val)
+    return out

@@ -12,10 +12,22 @@ import torch
 
 import oracle
 import paper_2602_11937_amd as pz
-from helpers import torch_decode_e4m3
+from helpers import paper_values, torch_decode_e4m3
 from workloads import bf16_bits, bf16_to_f32
 
 D, THETA, L0 = 64, 150000.0, 4096
+
+
+def test_defaults_are_the_papers_yarn_factor_and_contexts():
+    pv = paper_values()
+    assert pv["yarn_factor"] == 56 and pv["yarn_factor_parent"] == 32
+    # 32 is the nominal extension ratio of the parent: original context x 32 = extended context
+    assert pv["yarn_original_context"] * pv["yarn_factor_parent"] == pv["yarn_extended_context"]
+    prm = pz.YarnParams()
+    assert prm.factor == pv["yarn_factor"] and prm.original_context == pv["yarn_original_context"] == L0
+    c_def, s_def = oracle.yarn_table(D, 3)
+    c_56, s_56 = oracle.yarn_table(D, 3, theta=THETA, factor=pv["yarn_factor"], original_context=L0)
+    assert np.array_equal(c_def, c_56) and np.array_equal(s_def, s_56)
 
 
 def angles(cos, sin, t):

@@ -9,12 +9,19 @@ capacity of the cache (Section 3, "KV Quantization").
 import numpy as np
 
 import workloads as wl
+from helpers import paper_values
+
+PV = paper_values()
 
 
 def test_layer_pattern_counts():
     pat = wl.layer_pattern()
-    assert len(pat) == 36
-    assert pat.count(128) == 18 and pat.count(8192) == 8 and pat.count(0) == 10
+    n_layers, n_full, n_conv = (int(PV[k]) for k in ("parent_attention_layers", "parent_full_attention_layers",
+                                                     "converted_layers"))
+    w_par, w_conv = int(PV["parent_window_tokens"]), int(PV["converted_window_tokens"])
+    assert (n_layers, n_full, n_conv, w_par, w_conv) == (36, 18, 8, 128, 8192)
+    assert len(pat) == n_layers
+    assert pat.count(w_par) == n_layers - n_full and pat.count(w_conv) == n_conv and pat.count(0) == n_full - n_conv
     assert all(w == 128 for w in pat[0::2]) and all(w in (0, 8192) for w in pat[1::2])
     assert pat == wl.layer_pattern()                          # seeded, reproducible
     parent = wl.layer_pattern(n_converted=0)
@@ -22,12 +29,13 @@ def test_layer_pattern_counts():
 
 
 def test_kv_cache_is_about_forty_percent_smaller():
-    L = 131072                                                # 64K input + 64K output
+    L = int(PV["scenario_input_tokens"] + PV["scenario_output_tokens"])
+    assert L == 131072
     child = sum(wl.kv_tokens_read([L], w) for w in wl.layer_pattern())
     parent = sum(wl.kv_tokens_read([L], w) for w in wl.layer_pattern(n_converted=0))
     assert child == 10 * L + 8 * 8192 + 18 * 128 and parent == 18 * L + 18 * 128
     assert abs(child / parent - 0.5837) < 1e-3                # 41.6 % smaller: the paper's "40 %"
-    assert 0.38 < 1 - child / parent < 0.44
+    assert abs((1 - child / parent) - PV["kv_cache_fraction_saved"]) < 0.03     # the paper rounds to 40 %
     lens = wl.ragged_lengths(5, 32, 1024, 131072)
     r = (sum(wl.kv_tokens_read(lens, w) for w in wl.layer_pattern())
          / sum(wl.kv_tokens_read(lens, w) for w in wl.layer_pattern(n_converted=0)))
@@ -36,6 +44,7 @@ def test_kv_cache_is_about_forty_percent_smaller():
 
 def test_bytes_per_cached_token():
     assert wl.kv_bytes_per_token(8, 64, 1) == 1024 and wl.kv_bytes_per_token(8, 64, 2) == 2048
+    assert wl.kv_bytes_per_token(8, 64, 2) == PV["fp8_token_capacity_factor"] * wl.kv_bytes_per_token(8, 64, 1)
     assert wl.kv_tokens_read([100, 5000, 9000], 8192) == 100 + 5000 + 8192
     assert wl.kv_tokens_read([100, 5000, 9000], 0) == 14100
 
