@@ -38,7 +38,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        # PZ_ORACLE_LIB: load this prebuilt oracle library instead (the test that plants mistakes into
+        # copies of pz_oracle.c runs the pins against those copies this way)
+        L = C.CDLL(os.environ.get("PZ_ORACLE_LIB") or build())
         L.pzo_bf16_to_f32.restype = C.c_float
         L.pzo_bf16_to_f32.argtypes = [C.c_uint16]
         L.pzo_f32_to_bf16.restype = C.c_uint16

@@ -157,6 +157,32 @@ def test_quantize_is_one_division_then_encode():
     assert np.array_equal(oracle.quantize(xb, 1.0), oracle.e4m3_encode(bf16_to_f32(xb)))
 
 
+def test_quantize_divides_and_does_not_multiply_by_the_reciprocal():
+    """x / scale and x * (1 / scale) differ by an ulp now and then, and when the quotient sits on the
+    midpoint between two codes that ulp decides the code.  Such inputs are built on purpose: for a
+    bf16 x and a midpoint mid, scales within a few ulps of x / mid put the quotient on or beside mid.
+    The cases where numpy's IEEE fp32 division and the reciprocal product give different codes (by
+    PyTorch's conversion) are kept, and the oracle must side with the division on every one."""
+    x = bf16_to_f32(np.arange(0x3F80, 0x4080, dtype=np.uint16))               # bf16 values in [1, 4)
+    found = []
+    for code in range(0x30, 0x60):                                             # midpoints above codes of 0.25 .. 28
+        mid = np.float32((float(exact_value(code)) + float(exact_value(code + 1))) / 2)
+        s0 = (x / mid).astype(np.float32)
+        for ds in range(-3, 4):
+            sc = (s0.view(np.int32) + np.int32(ds)).view(np.float32)
+            r1 = x / sc
+            r2 = x * (np.float32(1.0) / sc)
+            idx = np.nonzero(r1 != r2)[0]
+            c1 = torch.from_numpy(r1[idx]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            c2 = torch.from_numpy(r2[idx]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            for i in idx[c1 != c2]:
+                found.append((int(bf16_bits(x[i:i + 1])[0]), float(sc[i]), float(r1[i]), float(r2[i])))
+    assert len(found) >= 50, len(found)
+    for xb, sc, r1, r2 in found[:300]:
+        got = int(oracle.quantize(np.array([xb], dtype=np.uint16), sc)[0])
+        assert got == nearest_code(r1) and got != nearest_code(r2), (hex(xb), sc)
+
+
 def test_power_of_two_scale_only_shifts_the_exponent():
     """With a power-of-two scale the rounding is that of the unscaled value: the code's exponent
     field moves by -log2(scale) and the mantissa bits are unchanged, whenever both the scaled and
