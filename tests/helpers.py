@@ -74,3 +74,32 @@ def paper_values():
                 key, val = (x.strip() for x in line.split("=", 1))
                 out[key] = float(val)
     return out
+
+
+def division_sensitive_inputs():
+    """(bf16 bits of x, scale, fl(x / scale), fl(x * fl(1 / scale))) where the two quotients quantise to
+    different E4M3 codes: for a bf16 x in [1, 4) and the midpoint between two adjacent codes, scales
+    within a few ulps of x / midpoint put the quotient on or beside the midpoint, where one ulp decides
+    the code.  Quotients by numpy's IEEE fp32 arithmetic, codes by PyTorch's float8 conversion."""
+    import torch
+    from workloads import bf16_bits, bf16_to_f32
+
+    def code_value(c):
+        e, m = (c >> 3) & 15, c & 7
+        return m * 2.0 ** -9 if e == 0 else (8 + m) * 2.0 ** (e - 10)
+
+    x = bf16_to_f32(np.arange(0x3F80, 0x4080, dtype=np.uint16))
+    found = []
+    for code in range(0x30, 0x60):                                  # midpoints above the codes of 0.25 .. 28
+        mid = np.float32((code_value(code) + code_value(code + 1)) / 2)
+        s0 = (x / mid).astype(np.float32)
+        for ds in range(-3, 4):
+            sc = (s0.view(np.int32) + np.int32(ds)).view(np.float32)
+            r1 = x / sc
+            r2 = x * (np.float32(1.0) / sc)
+            idx = np.nonzero(r1 != r2)[0]
+            c1 = torch.from_numpy(r1[idx]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            c2 = torch.from_numpy(r2[idx]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            for i in idx[c1 != c2]:
+                found.append((int(bf16_bits(x[i:i + 1])[0]), float(sc[i]), float(r1[i]), float(r2[i])))
+    return found

@@ -61,6 +61,32 @@ def test_append_every_bf16_value_and_negative_slots():
         assert np.array_equal(gv[~nan_v], ov[~nan_v]) and np.all((gv[nan_v] & 0x7F) == 0x7F)
 
 
+def test_append_divides_on_inputs_where_the_reciprocal_product_gives_another_code():
+    """Inputs whose quotient sits on a midpoint between two codes, so that x * (1 / scale) and x / scale
+    quantise differently: the kernel must produce the division's code, as the oracle does."""
+    from helpers import division_sensitive_inputs
+    cases = division_sensitive_inputs()
+    by_scale = {}
+    for xb, sc, _, _ in cases:
+        by_scale.setdefault(sc, []).append(xb)
+    scales = sorted(by_scale, key=lambda s: -len(by_scale[s]))[:40]
+    Hkv, d, P = 1, 64, 16
+    n_checked = 0
+    for sc in scales:
+        xs = by_scale[sc]
+        row = np.resize(np.array(xs, dtype=np.uint16), (1, Hkv, d))           # the scale's inputs, repeated
+        neg = row | 0x8000                                                     # and their negatives for V
+        cache = pz.PagedCache.allocate(1, P, Hkv, d, pz.KV_FP8, DEV, fill=0xAA)
+        pz.pz_kv_append_fp8(cache, dev_bits(row), dev_bits(neg), torch.tensor([3], dtype=torch.int64, device=DEV),
+                            1, sc, sc)
+        torch.cuda.synchronize()
+        gk, gv = to_oracle_layout(cache)
+        want = oracle.quantize(row.ravel(), sc)
+        assert np.array_equal(gk[3, 0], want) and np.array_equal(gv[3, 0], want | 0x80), sc
+        n_checked += len(xs)
+    assert n_checked >= 40
+
+
 def test_append_bf16_cache_copies_bits():
     case = wl.make_case("b", B=2, Hq=8, Hkv=2, d=64, P=32, seq_lens=[70, 33], seed=1)
     cache = gpu_cache(case, dtype=pz.KV_BF16)
@@ -122,6 +148,34 @@ def test_attention_matches_oracle(name, split_tokens):
     e32, e64 = rel_err(got, want), rel_err(got, oracle_attn(case, kc, vc, accum="f64"))
     print("%s split=%d: err vs f32 oracle %.2e, vs f64 oracle %.2e" % (name, split_tokens, e32, e64))
     assert e32 <= TOL and e64 <= TOL
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_match_oracle(seed):
+    """Seeded random geometry: heads, group size (also the two-virtual-head groups above 8), page size,
+    batch, lengths (zero and one included), window, chunk length, sinks on or off."""
+    rng = np.random.default_rng(1000 + seed)
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 16]))
+    P = int(rng.choice([16, 32, 64]))
+    B = int(rng.integers(1, 6))
+    lens = rng.integers(0, 3000 if Hkv * G <= 32 else 700, size=B)
+    lens[rng.integers(0, B)] = int(rng.choice([0, 1, 63, 64, 65]))
+    if lens.sum() == 0:
+        lens[0] = 200
+    window = int(rng.choice([0, 0, int(rng.integers(1, 2000))]))
+    split = int(rng.choice([0, 64, 128, 192, 1024]))
+    case = wl.make_case("r%d" % seed, B=B, Hq=Hkv * G, Hkv=Hkv, d=64, P=P, seq_lens=lens.tolist(), window=window,
+                        sinks=bool(rng.integers(0, 2)), seed=2000 + seed)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    want = oracle_attn(case, kc, vc, accum="f64")
+    got = gpu_attn(case, cache, split_tokens=split)
+    err = rel_err(got, want)
+    print("seed %d: Hkv=%d G=%d P=%d lens=%s window=%d split=%d err=%.2e" % (seed, Hkv, G, P, lens.tolist(), window,
+                                                                             split, err))
+    assert not np.any(np.isnan(got)) and err <= TOL
+    assert np.all(got[lens == 0] == 0)
 
 
 def test_zero_length_rows_and_garbage_beyond_the_context():

@@ -14,6 +14,7 @@ import pytest
 import torch
 
 import oracle
+from helpers import division_sensitive_inputs
 from workloads import bf16_bits, bf16_to_f32
 
 ALL_CODES = np.arange(256, dtype=np.uint8)
@@ -163,20 +164,7 @@ def test_quantize_divides_and_does_not_multiply_by_the_reciprocal():
     bf16 x and a midpoint mid, scales within a few ulps of x / mid put the quotient on or beside mid.
     The cases where numpy's IEEE fp32 division and the reciprocal product give different codes (by
     PyTorch's conversion) are kept, and the oracle must side with the division on every one."""
-    x = bf16_to_f32(np.arange(0x3F80, 0x4080, dtype=np.uint16))               # bf16 values in [1, 4)
-    found = []
-    for code in range(0x30, 0x60):                                             # midpoints above codes of 0.25 .. 28
-        mid = np.float32((float(exact_value(code)) + float(exact_value(code + 1))) / 2)
-        s0 = (x / mid).astype(np.float32)
-        for ds in range(-3, 4):
-            sc = (s0.view(np.int32) + np.int32(ds)).view(np.float32)
-            r1 = x / sc
-            r2 = x * (np.float32(1.0) / sc)
-            idx = np.nonzero(r1 != r2)[0]
-            c1 = torch.from_numpy(r1[idx]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
-            c2 = torch.from_numpy(r2[idx]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
-            for i in idx[c1 != c2]:
-                found.append((int(bf16_bits(x[i:i + 1])[0]), float(sc[i]), float(r1[i]), float(r2[i])))
+    found = division_sensitive_inputs()
     assert len(found) >= 50, len(found)
     for xb, sc, r1, r2 in found[:300]:
         got = int(oracle.quantize(np.array([xb], dtype=np.uint16), sc)[0])
