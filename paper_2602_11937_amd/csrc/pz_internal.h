@@ -46,7 +46,9 @@ struct AppendParams {
     float k_scale, v_scale;
 };
 
-#define PZ_PREFILL_NT 2          // column tiles per wave of the prefill kernel: 2 * NT query tokens
+#ifndef PZ_PREFILL_NT
+#define PZ_PREFILL_NT 3          // column tiles per wave of the prefill kernel: 2 * NT query tokens
+#endif
 
 struct PrefillParams {
     const uint8_t *k;

@@ -18,8 +18,12 @@
 
 namespace {
 
+// Two waves per SIMD is the register budget (256 per lane): stating it keeps every matrix-core
+// accumulator in the ordinary vector registers.  Without the bound the compiler parks accumulators
+// in the accumulation registers and copies each one back before the softmax reads it (72 extra
+// VALU instructions per 64-position step in a kernel whose VALUs are the bottleneck).
 template <int P, int EB, int NT>
-__global__ __launch_bounds__(64) void prefill_attn_kernel(const pz::PrefillParams prm) {
+__global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillParams prm) {
     constexpr int NPS = 64 / P;
     constexpr int GROUP = 64 / NPS;                    // steps whose page ids fit one register
     constexpr int QT = 2 * NT;                         // query tokens per wave
