@@ -324,7 +324,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             return;
         }
         // burst the parked partials out: 16 lanes cover one 256-byte row, a wave-wide store covers
-        // 4 rows.  Chunks of the group that lie beyond the context were never parked and are not
+        // 4 rows.  The stores are non-temporal: the partials are read once, by another kernel, and
+        // written through they do not wait in L2 for the write-back at the end of the kernel.  Chunks of the group that lie beyond the context were never parked and are not
         // written: the merge kernel bounds its reads by the sequence length.
         __syncthreads();                               // lanes read what other lanes parked
         const int n_rows = (next_chunk - c_first) * G;
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                 if (r < n_rows) {
                     const int cl = r / G, h = r - cl * G;
                     const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c_first + cl;
-                    *reinterpret_cast<f32x4 *>(prm.ws_acc + row * 64 + 4 * quad) = x[u];
+                    __builtin_nontemporal_store(x[u], reinterpret_cast<f32x4 *>(prm.ws_acc + row * 64 + 4 * quad));
                 }
             }
         }
@@ -354,7 +355,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             float2 ml;
             ml.x = lds[cl * 528 + 512 + h];
             ml.y = lds[cl * 528 + 520 + h];
-            *reinterpret_cast<float2 *>(prm.ws_ml + row * 2) = ml;
+            __builtin_nontemporal_store(ml.x, prm.ws_ml + row * 2);
+            __builtin_nontemporal_store(ml.y, prm.ws_ml + row * 2 + 1);
         }
         return;
     }
