@@ -142,6 +142,18 @@ class Layer:
                           lay.sinks, lay.sm_scale, self.k_scale, self.v_scale, self.window, self.split, self.S,
                           self.ws if self.split else None, self.ws_bytes, self.out)
 
+    def attn_append(self):
+        """The append of the step's new token fused into the attention launch."""
+        lay, pz = self.lay, self.pz
+        pz.pz_decode_attn_append(self.cache, lay.k_new, lay.v_new, lay.q, lay.block_table, self.max_pages,
+                                 lay.seq_lens_dev, lay.B, lay.Hq, lay.sinks, lay.sm_scale, self.k_scale, self.v_scale,
+                                 self.window, self.split, self.S, self.ws if self.split else None, self.ws_bytes,
+                                 self.out)
+
+    def step_fused(self):
+        self.attn_append()
+        self.reduce()
+
     def reduce(self):
         if not self.split:
             return
@@ -157,6 +169,18 @@ class Layer:
         if ev is not None:
             ev[1].record()
         self.reduce()
+
+
+def time_fused(torch, layers, steps, warmup):
+    """The same K steps with two launches each: pz_decode_attn_append + merge."""
+    for i in range(warmup):
+        layers[i % len(layers)].step_fused()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        layers[(warmup + i) % len(layers)].step_fused()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
 
 
 def time_steps(torch, layers, steps, warmup, events):
@@ -281,6 +305,19 @@ class Model:
                 l.step()
 
 
+def time_model_fused(torch, model, steps, warmup):
+    for _ in range(warmup):
+        for l in model.layers:
+            l.step_fused()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for l in model.layers:
+            l.step_fused()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def time_model(torch, model, steps, warmup, events):
     for _ in range(warmup):
         model.step()
@@ -329,6 +366,11 @@ def run_cfg5(args, pz, wl, torch):
                      "frac": full_bytes / (kern_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, "kernel_us_avg": kern_avg * 1e3,
                      "ms_per_step_with_events": ms_ev, "algorithmic_bytes_per_launch": full_bytes, "traffic": None},
     }
+    ms_f = time_model_fused(torch, model, args.steps, args.warmup)
+    result["fused_append"] = {"ms_per_step": ms_f, "GBps": step_bytes / (ms_f * 1e-3) / 1e9,
+                              "pct_hbm_peak": 100.0 * step_bytes / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                              "attn_tokens_per_s": B / (ms_f * 1e-3),
+                              "launches": "per layer pz_decode_attn_append (+ pz_decode_attn_splitk_reduce): 54 per step"}
     graph = capture(torch, model.step)                            # all 90 launches of the step in one HIP graph
     ms_g = time_graphs(torch, [graph], args.steps, args.warmup)
     result["hip_graph"] = {"ms_per_step": ms_g, "GBps": step_bytes / (ms_g * 1e-3) / 1e9,
@@ -584,6 +626,12 @@ def main():
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload) if args.split_tokens is None else None},
     }
+    ms_f = time_fused(torch, layers, args.steps, args.warmup)
+    result["fused_append"] = {"ms_per_step": ms_f, "GBps": step_bytes / (ms_f * 1e-3) / 1e9,
+                              "pct_hbm_peak": 100.0 * step_bytes / (ms_f * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                              "attn_tokens_per_s": B / (ms_f * 1e-3),
+                              "launches": "pz_decode_attn_append + pz_decode_attn_splitk_reduce"
+                              if spec["split_tokens"] else "pz_decode_attn_append"}
     # the box's plain streaming-read rate over the very same cache bytes: the library's amax kernel
     # (16-byte loads, a max per element, nothing written) run over the K and V arrays of each instance
     if args.workload in ("cfg3", "cfg2"):

@@ -149,6 +149,28 @@ pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
                          size_t workspace_bytes, void *out, int32_t out_dtype, void *hip_stream);
 
 /*
+ * pz_kv_append_fp8 of one new token per sequence fused into pz_decode_attn (one launch less per
+ * decode step: at decode sizes the append is launch-bound).  The paper's decode step quantises the
+ * new token's K/V into the FP8 cache and then attends over the cache including that token (Section 3,
+ * "KV Quantization"); this call does both, with the same arithmetic and the same bytes as the two
+ * separate calls.
+ *
+ *   k_new, v_new : bf16 [batch][n_kv_heads][head_dim]; row b is written to the slot of position
+ *                  L_b - 1 of sequence b, i.e. block_table[b][(L_b-1)/page_size] * page_size +
+ *                  (L_b-1) % page_size (so that entry of the block table must be valid), quantised
+ *                  with k_scale / v_scale exactly as pz_kv_append_fp8 does (bf16 caches: copied)
+ * Sequences with L_b == 0 append nothing.  Everything else, including the split-K protocol, as in
+ * pz_decode_attn.  The cache must not be read or written by other work on the device while the
+ * call runs (inside the call only the workgroup that attends position L_b - 1 touches its bytes).
+ */
+pz_status pz_decode_attn_append(const pz_cache *cache /* host */, const void *k_new, const void *v_new,
+                                const void *q, const int32_t *block_table, int32_t max_pages_per_seq,
+                                const int32_t *seq_lens, int32_t batch, int32_t n_q_heads,
+                                const float *sinks, float sm_scale, float k_scale, float v_scale,
+                                int32_t window, int32_t split_tokens, int32_t n_splits, void *workspace,
+                                size_t workspace_bytes, void *out, int32_t out_dtype, void *hip_stream);
+
+/*
  * Second pass of split-K: log-sum-exp merge of the partials, sink, normalisation.
  *     M = max(sink_h, max_i m_i);  D = exp(sink_h - M) + sum_i l_i exp(m_i - M)
  *     out[b][h][c] = v_scale * sum_i acc_i[c] exp(m_i - M) / D

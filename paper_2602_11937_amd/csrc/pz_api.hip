@@ -118,12 +118,15 @@ size_t pz_decode_attn_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t 
     return (size_t)batch * (size_t)n_q_heads * (size_t)n_splits * (size_t)(head_dim + 2) * sizeof(float);
 }
 
-pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *block_table,
-                         int32_t max_pages_per_seq, const int32_t *seq_lens, int32_t batch,
-                         int32_t n_q_heads, const float *sinks, float sm_scale, float k_scale,
-                         float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits,
-                         void *workspace, size_t workspace_bytes, void *out, int32_t out_dtype,
-                         void *hip_stream) {
+namespace {
+
+pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void *v_new, bool fused_append,
+                           const void *q, const int32_t *block_table,
+                           int32_t max_pages_per_seq, const int32_t *seq_lens, int32_t batch,
+                           int32_t n_q_heads, const float *sinks, float sm_scale, float k_scale,
+                           float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits,
+                           void *workspace, size_t workspace_bytes, void *out, int32_t out_dtype,
+                           void *hip_stream) {
     const pz_status cs = check_cache(cache);
     if (cs != PZ_OK) return cs;
     if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || split_tokens < 0)
@@ -136,6 +139,7 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     if (split_tokens % 64 != 0) return PZ_ERR_UNSUPPORTED;
     if (batch == 0) return PZ_OK;
     if (q == nullptr || block_table == nullptr || seq_lens == nullptr) return PZ_ERR_NULL;
+    if (fused_append && (k_new == nullptr || v_new == nullptr)) return PZ_ERR_NULL;
     if (split_tokens > 0) {
         if (n_splits <= 0) return PZ_ERR_SHAPE;
         if (workspace == nullptr) return PZ_ERR_WORKSPACE;
@@ -148,8 +152,11 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     if ((int64_t)batch * cache->n_kv_heads * 2 * n_chunks > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
 
     pz::AttnParams p;
-    p.k = static_cast<const uint8_t *>(cache->k);
-    p.v = static_cast<const uint8_t *>(cache->v);
+    p.k = static_cast<uint8_t *>(cache->k);
+    p.v = static_cast<uint8_t *>(cache->v);
+    p.k_new = fused_append ? static_cast<const uint16_t *>(k_new) : nullptr;
+    p.v_new = fused_append ? static_cast<const uint16_t *>(v_new) : nullptr;
+    p.k_scale = k_scale;
     p.q = static_cast<const uint16_t *>(q);
     p.block_table = block_table;
     p.seq_lens = seq_lens;
@@ -184,6 +191,30 @@ pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *bl
     const hipError_t e = pz::launch_decode_attn(p, cache->page_size, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
                                                 n_waves, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
+}
+
+}  // namespace
+
+pz_status pz_decode_attn(const pz_cache *cache, const void *q, const int32_t *block_table,
+                         int32_t max_pages_per_seq, const int32_t *seq_lens, int32_t batch,
+                         int32_t n_q_heads, const float *sinks, float sm_scale, float k_scale,
+                         float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits,
+                         void *workspace, size_t workspace_bytes, void *out, int32_t out_dtype,
+                         void *hip_stream) {
+    return decode_attn_impl(cache, nullptr, nullptr, false, q, block_table, max_pages_per_seq, seq_lens, batch,
+                            n_q_heads, sinks, sm_scale, k_scale, v_scale, window, split_tokens, n_splits, workspace,
+                            workspace_bytes, out, out_dtype, hip_stream);
+}
+
+pz_status pz_decode_attn_append(const pz_cache *cache, const void *k_new, const void *v_new, const void *q,
+                                const int32_t *block_table, int32_t max_pages_per_seq, const int32_t *seq_lens,
+                                int32_t batch, int32_t n_q_heads, const float *sinks, float sm_scale,
+                                float k_scale, float v_scale, int32_t window, int32_t split_tokens,
+                                int32_t n_splits, void *workspace, size_t workspace_bytes, void *out,
+                                int32_t out_dtype, void *hip_stream) {
+    return decode_attn_impl(cache, k_new, v_new, true, q, block_table, max_pages_per_seq, seq_lens, batch,
+                            n_q_heads, sinks, sm_scale, k_scale, v_scale, window, split_tokens, n_splits, workspace,
+                            workspace_bytes, out, out_dtype, hip_stream);
 }
 
 pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_bytes, int32_t batch,

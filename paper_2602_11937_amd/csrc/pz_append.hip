@@ -1,10 +1,8 @@
 // Quantise-and-append kernel for gfx950: new K/V rows (bf16) -> paged cache (E4M3 or bf16).
 //
 // Operation: code = e4m3(x / scale), round to nearest even, saturating at +-448 (paper
-// Section 3, "KV Quantization": FP8 KV cache with max-calibrated per-layer K and V scales).
-// The division is a correctly rounded fp32 division; the hardware convert
-// (v_cvt_pk_fp8_f32) rounds to nearest even but turns out-of-range inputs into NaN, so the
-// quotient is clamped to +-448 first (NaN inputs bypass the clamp and stay NaN).
+// Section 3, "KV Quantization": FP8 KV cache with max-calibrated per-layer K and V scales); the
+// arithmetic of one value is in pz_quant.h.
 //
 // Work split: one workgroup = up to 64 tokens of one KV head.
 //   K ([page][head][P][64]): 4 threads per token, 16 channels each -> one 16-byte store; the 16
@@ -15,6 +13,7 @@
 #include <stdint.h>
 
 #include "pz_internal.h"
+#include "pz_quant.h"
 
 namespace {
 
@@ -22,22 +21,12 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 __device__ __forceinline__ float bf16_to_f32(unsigned bits16) { return __uint_as_float(bits16 << 16); }
 
-__device__ __forceinline__ float scaled_clamped(float x, float scale) {
-    const float r = __fdiv_rn(x, scale);
-    return (r != r) ? r : __builtin_amdgcn_fmed3f(r, -448.0f, 448.0f);
-}
-
 // two bf16 values packed in one dword -> two E4M3 codes in the low (hi=false) or high word of old
 __device__ __forceinline__ unsigned quant_pair(unsigned packed_bf16, float scale, unsigned old, bool hi) {
     const float a = scaled_clamped(bf16_to_f32(packed_bf16 & 0xffffu), scale);
     const float b = scaled_clamped(bf16_to_f32(packed_bf16 >> 16), scale);
     return hi ? (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
               : (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
-}
-
-__device__ __forceinline__ unsigned quant_one(unsigned bits16, float scale) {
-    const float a = scaled_clamped(bf16_to_f32(bits16), scale);
-    return (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, a, 0, false) & 0xffu;
 }
 
 template <int EB>

@@ -32,6 +32,7 @@
 
 #include "pz_attn_common.h"
 #include "pz_internal.h"
+#include "pz_quant.h"
 
 namespace {
 
@@ -312,6 +313,33 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                 };
                 load_k<P, EB>(kt, k_page(gs), geom.koff);
                 load_v<P, EB>(vt, v_page(gs), geom.voff);
+                // Fused append: the wave whose steps include position L - 1 writes the newest token's
+                // K/V (lane = channel) before it gets there.  It is placed after the first loads so
+                // that the block-table read it needs overlaps with them.  The writes and the later
+                // loads of the same bytes belong to this one wave and are kept in program order by
+                // the hardware; the explicit wait covers the case where that step is the first one.
+                if (gs == s0 && prm.k_new != nullptr && s1 > ((L - 1) >> 6) && j1 == L) {
+                    const int pos = L - 1;
+                    const int64_t page = bt[pos / P];
+                    const int off = pos % P;
+                    const int gc = g >> prm.head_shift;
+                    const int64_t src = ((int64_t)b * prm.cache_heads + gc) * 64 + lane;
+                    const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
+                    uint8_t *kd = prm.k + (((page * prm.cache_heads + gc) * P + off) * 64 + lane) * EB;
+                    uint8_t *vd = prm.v + (((page * prm.cache_heads + gc) * 64 + lane) * P + off) * EB;
+                    if constexpr (EB == 1) {
+                        *kd = (uint8_t)quant_one(kb16, prm.k_scale);
+                        *vd = (uint8_t)quant_one(vb16, prm.v_scale);
+                    } else {
+                        *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
+                        *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
+                    }
+                    if (((L - 1) >> 6) == gs) {                    // the step just loaded holds position L - 1
+                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                        load_k<P, EB>(kt, k_page(gs), geom.koff);
+                        load_v<P, EB>(vt, v_page(gs), geom.voff);
+                    }
+                }
                 for (int s = gs; s + 1 < ge; ++s) step(s, true);
                 step(ge - 1, false);
             }

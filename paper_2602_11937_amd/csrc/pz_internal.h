@@ -8,8 +8,8 @@
 namespace pz {
 
 struct AttnParams {
-    const uint8_t *k;            // K cache  [page][Hkv][P][64]
-    const uint8_t *v;            // V cache  [page][Hkv][64][P]
+    uint8_t *k;                  // K cache  [page][Hkv][P][64]   (written only by the fused append)
+    uint8_t *v;                  // V cache  [page][Hkv][64][P]
     const uint16_t *q;           // bf16 [B][Hq][64]
     const int32_t *block_table;  // [B][max_pages]
     const int32_t *seq_lens;     // [B]
@@ -17,6 +17,11 @@ struct AttnParams {
     float *ws_acc;               // split-K partials [B][Hq][S][64]
     float *ws_ml;                // [B][Hq][S][2]
     void *out;                   // [B][Hq][64]
+    // fused append (both nullptr: none): the newest token's K/V rows, bf16 [B][cache_heads][64]; the
+    // workgroup wave that attends position L_b - 1 writes them into the cache before it reads that step
+    const uint16_t *k_new;
+    const uint16_t *v_new;
+    float k_scale;               // for the fused append only (the logits use sc)
     int32_t max_pages, B, Hq, Hkv, G;   // Hkv, G: "virtual" KV heads of at most 8 query heads each
     int32_t cache_heads, head_shift;    // KV heads of the cache; virtual head g reads cache head g >> head_shift
     int32_t window, split_tokens, n_splits, out_dtype;

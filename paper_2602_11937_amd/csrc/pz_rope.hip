@@ -17,6 +17,7 @@
 #include <stdint.h>
 
 #include "pz_internal.h"
+#include "pz_quant.h"
 
 namespace {
 
@@ -30,11 +31,6 @@ __device__ __forceinline__ unsigned bf16_rne(float x) {
     unsigned u = __float_as_uint(x);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-__device__ __forceinline__ float scaled_clamped(float x, float scale) {
-    const float r = __fdiv_rn(x, scale);
-    return (r != r) ? r : __builtin_amdgcn_fmed3f(r, -448.0f, 448.0f);
 }
 
 // rotate the 8 channel pairs (i, i+32), i = 8*part .. 8*part+7, of one 64-channel bf16 row

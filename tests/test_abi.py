@@ -77,6 +77,26 @@ def test_decode_attn_rejects_bad_arguments_before_any_launch():
     assert attn(cache(), batch=0) == 0                               # nothing to do is not an error
 
 
+def test_fused_append_call_validates_like_the_plain_call():
+    NULL, SHAPE, UNSUP = -1, -2, -3
+
+    def fused(c, k_new=0x50, v_new=0x60, **kw):
+        a = dict(q=0x10, block_table=0x20, max_pages=4, seq_lens=0x30, batch=2, n_q_heads=64, sinks=None,
+                 sm_scale=0.125, k_scale=0.01, v_scale=0.01, window=0, split_tokens=0, n_splits=0, workspace=None,
+                 workspace_bytes=0, out=0x40, out_dtype=0)
+        a.update(kw)
+        return pz.pz_decode_attn_append(c, k_new, v_new, a["q"], a["block_table"], a["max_pages"], a["seq_lens"],
+                                        a["batch"], a["n_q_heads"], a["sinks"], a["sm_scale"], a["k_scale"],
+                                        a["v_scale"], a["window"], a["split_tokens"], a["n_splits"], a["workspace"],
+                                        a["workspace_bytes"], a["out"], a["out_dtype"], stream=0, check=False)
+
+    assert fused(cache(), k_new=None) == NULL and fused(cache(), v_new=None) == NULL
+    assert fused(cache(), q=None) == NULL and fused(None) == NULL
+    assert fused(cache(), n_q_heads=60) == SHAPE and fused(cache(head_dim=128)) == UNSUP
+    assert fused(cache(), k_scale=0.0) == SHAPE
+    assert fused(cache(), batch=0) == 0
+
+
 def test_append_and_reduce_reject_bad_arguments():
     def app(c, **kw):
         a = dict(k_new=0x10, v_new=0x20, slots=0x30, n=4, ks=0.01, vs=0.01)
