@@ -32,6 +32,11 @@ int env_int(const char *name, int fallback) {
     return v > 0 ? v : fallback;
 }
 
+bool env_is_zero(const char *name) {
+    const char *s = getenv(name);
+    return s != nullptr && s[0] == '0' && s[1] == 0;
+}
+
 int round_down_pow2(int x) {
     int r = 1;
     while (2 * r <= x) r *= 2;
@@ -188,8 +193,16 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     int n_waves = 1, chunks_per_group = 1;
     pick_shape(batch, p.Hkv, max_steps, n_chunks, &n_waves, &chunks_per_group);
     p.chunks_per_group = chunks_per_group;
-    const hipError_t e = pz::launch_decode_attn(p, cache->page_size, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
-                                                n_waves, static_cast<hipStream_t>(hip_stream));
+    const int elem_bytes = cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2;
+    hipError_t e;
+    // Full-attention split-K with one-wave workgroups: the chunks are dealt out evenly on the device from
+    // the actual lengths (PZ_ATTN_BALANCED=0 keeps the one-workgroup-per-chunk-group grid, for
+    // comparisons).  Window layers keep that grid: their sequences all span about the window, and
+    // their first and last chunks are short, which a partition by chunk count does not see.
+    if (split_tokens > 0 && window == 0 && n_waves == 1 && !env_is_zero("PZ_ATTN_BALANCED"))
+        e = pz::launch_decode_attn_balanced(p, cache->page_size, elem_bytes, static_cast<hipStream_t>(hip_stream));
+    else
+        e = pz::launch_decode_attn(p, cache->page_size, elem_bytes, n_waves, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
 }
 

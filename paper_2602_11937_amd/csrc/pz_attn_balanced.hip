@@ -1,0 +1,412 @@
+// Split-K decode attention with a balanced partition of the chunks for gfx950 (MI355X).
+//
+// Same operation and same per-step arithmetic as decode_attn_kernel (pz_attn.hip): single-token GQA
+// attention over the paged FP8 / bf16 cache, sliding window ("most recent W tokens", paper Section 2,
+// "Window attention for long-context inference"), sink-free partials (acc, m, l) per chunk of
+// split_tokens positions.  What differs is who does which chunk.  A launch grid can only be sized
+// from the longest sequence, so with one workgroup per (sequence, chunk group) a ragged batch
+// leaves many workgroups empty, the rest uneven, and the kernel ends in a long thin tail.  Here
+// every workgroup (one wave64) first reads all sequence lengths, counts the chunks that exist,
+//     n_b = min(n_splits, ceil((L_b - a_b) / split_tokens)),   tot = sum_b n_b,
+// and takes an equal share of the list (b, chunk) in sequence order for its KV head: with
+// k = ceil(tot / blocks_per_head) chunks in the largest share, n_act = ceil(tot / k) workgroups
+// are active and workgroup i owns list entries [i tot / n_act, (i+1) tot / n_act) -- k or k-1
+// chunks, and the few workgroups that differ have LESS work, so nothing is left over at the end.
+// A share may span several sequences; each run of chunks inside one sequence is streamed with
+// the register pipeline of pz_attn.hip, its partials parked in LDS and written out when the run
+// ends (or when 4 are parked).  The partition is a pure function of the lengths: no queue, no
+// atomics, nothing to wait for.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pz_attn_common.h"
+#include "pz_attn_steps.h"
+#include "pz_internal.h"
+#include "pz_quant.h"
+
+namespace {
+
+// Partials parked in LDS before a write-out.  A share holds more chunks than this only when the
+// batch has more chunks than 6 x the workgroups the device holds at once.
+constexpr int kPark = 6;
+
+// Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS traffic): four shifted adds
+// inside every row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then
+// lane 31 to rows 2 and 3.  Lane 63 ends up with the total.
+__device__ __forceinline__ int wave_inclusive_scan_int(int x) {
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, true);     // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, true);     // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, true);     // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, true);     // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);    // row_bcast:15 into rows 1 and 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);    // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// Three waves per SIMD is the register budget: with four the compiler spills in the run set-up, and the
+// partition never needs more than the workgroups that stream well together (two to three per SIMD).
+template <int P, int EB>
+__global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::AttnParams prm) {
+    constexpr int NPS = 64 / P;                        // pages per step
+    constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
+    extern __shared__ float lds[];                     // kPark records of 528 floats (8 x 64 acc, 8 m, 8 l)
+
+    const int lane = threadIdx.x;
+    const int n = lane & 15, kb = lane >> 4;
+    const int head = n & 7;
+    const int G = prm.G;
+    // share index fastest: neighbouring workgroups (which the dispatcher deals to different XCDs) work
+    // on the same KV head, so every XCD streams all heads, as it does in decode_attn_kernel
+    const int bph = gridDim.x / prm.Hkv;               // workgroups per KV head
+    const int i_blk = blockIdx.x % bph;
+    const int g = blockIdx.x / bph;
+    const int split = prm.split_tokens;
+    const int steps_per_chunk = split >> 6;
+
+    auto chunks_of = [&](int L) -> int {
+        if (L <= 0) return 0;
+        const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
+        const int span = L - (lo & ~63);
+        return min(prm.n_splits, (span + split - 1) / split);
+    };
+    // the share of this workgroup out of `tot` chunks: [begin, end) of the list, or nothing.  The host
+    // keeps batch * n_kv_heads * n_splits below 2^31, so 32-bit arithmetic is enough.
+    auto share = [&](unsigned tot, unsigned &begin, unsigned &end) -> bool {
+        if (tot == 0) return false;
+        // 4 chunks per workgroup while that still gives 2048 waves, fewer for small jobs
+        const unsigned want = min(4u, max(1u, tot * (unsigned)prm.Hkv / 2048u));
+        const unsigned cap = min((unsigned)bph, (tot + want - 1) / want);
+        const unsigned k = (tot + cap - 1) / cap;      // chunks of the largest shares
+        const unsigned n_act = (tot + k - 1) / k;
+        const unsigned i = (unsigned)i_blk;
+        if (i >= n_act) return false;
+        const unsigned q = tot / n_act, r = tot - q * n_act;   // the first r shares hold q + 1 = k chunks
+        begin = i * q + min(i, r);
+        end = begin + q + (i < r ? 1u : 0u);
+        return true;
+    };
+
+    // Before the lengths are known: if every sequence had the longest length this workgroup would
+    // start at (spec_b, spec_c); the block-table entries of that place are fetched beside the
+    // lengths and used when the guess holds (it always does for a uniform batch).
+    int spec_b = -1, spec_c = 0, early0 = 0, early1 = 0;
+    if (prm.window == 0) {
+        unsigned sb, se;
+        if (share((unsigned)prm.B * (unsigned)prm.n_splits, sb, se)) {
+            spec_b = (int)(sb / (unsigned)prm.n_splits);
+            spec_c = (int)(sb - (unsigned)spec_b * (unsigned)prm.n_splits);
+            const int32_t *row = prm.block_table + (int64_t)spec_b * prm.max_pages;
+            const int p0 = spec_c * steps_per_chunk * NPS;
+            early0 = row[min(p0 + lane, prm.max_pages - 1)];
+            early1 = row[min(p0 + 64 + lane, prm.max_pages - 1)];
+        }
+    }
+
+    // chunk count of the batch and, for a batch of at most 64 sequences, its prefix sums
+    unsigned tot = 0;
+    int nn0 = 0, incl0 = 0;
+    for (int base = 0; base < prm.B; base += 64) {
+        const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
+        const int nn = chunks_of(L);
+        const int incl = wave_inclusive_scan_int(nn);
+        if (base == 0) {
+            nn0 = nn;
+            incl0 = incl;
+        }
+        tot += __builtin_amdgcn_readlane(incl, 63);     // uniform: stays scalar
+    }
+    unsigned c_begin, c_end;
+    if (!share(tot, c_begin, c_end)) return;
+
+    // the sequence that holds list entry c_begin, and the chunk inside it
+    int b = 0, c = 0;
+    {
+        unsigned run = 0;
+        for (int base = 0; base < prm.B; base += 64) {
+            int nn = nn0, incl = incl0;
+            if (base > 0) {
+                const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
+                nn = chunks_of(L);
+                incl = wave_inclusive_scan_int(nn);
+            }
+            const uint64_t past = __ballot(run + (unsigned)incl > c_begin);
+            if (past != 0) {
+                const int l0 = __builtin_ctzll(past);
+                b = base + l0;
+                c = (int)(c_begin - (run + __builtin_amdgcn_readlane(incl, l0) - __builtin_amdgcn_readlane(nn, l0)));
+                break;
+            }
+            run += __builtin_amdgcn_readlane(incl, 63);
+        }
+        b = min(b, prm.B - 1);                         // c_begin < tot puts (b, c) inside the batch anyway
+        c = max(c, 0);
+    }
+
+    const unsigned lo_mask = (n >= 8) ? 0xffff0000u : 0u;
+    const LaneGeom geom = lane_geom<P, EB>(lane);
+    const int64_t page_bytes = (int64_t)prm.cache_heads * P * 64 * EB;
+    const uint8_t *kbase = prm.k + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
+    const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
+    const float sc = prm.sc;
+    const int qh = g * G + head;                       // only meaningful when head < G
+
+    WaveState st;
+    auto reset_state = [&]() {
+        st.m = -INFINITY;
+        st.l = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) st.o[cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+    };
+    reset_state();
+
+    // park the state as partial number `slot` in LDS and reset it
+    auto park = [&](int slot) {
+        const float l = add_ror8(st.l[0]);             // both P halves, all 64 positions of every step
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            f32x4 x;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) x[r] = add_ror8(st.o[cc][r]);
+            if (n < 8 && head < G) *reinterpret_cast<f32x4 *>(&lds[slot * 528 + n * 64 + 16 * cc + 4 * kb]) = x;
+        }
+        if (lane < 8) {
+            lds[slot * 528 + 512 + lane] = st.m * kLn2;
+            lds[slot * 528 + 520 + lane] = l;
+        }
+        reset_state();
+    };
+    // write the parked partials of chunks [chunk0, chunk0 + count) of sequence bb out: 16 lanes cover
+    // one 256-byte row, a wave-wide store covers 4 rows.  Non-temporal: read once, by the merge kernel.
+    auto write_out = [&](int bb, int chunk0, int count) {
+        __syncthreads();                               // lanes read what other lanes parked
+        const int n_rows = count * G;
+        const int quad = lane & 15;
+        for (int r0 = 0; r0 < n_rows; r0 += 16) {
+            f32x4 x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = min(r0 + 4 * u + (lane >> 4), n_rows - 1);
+                const int cl = r / G, h = r - cl * G;
+                x[u] = *reinterpret_cast<const f32x4 *>(&lds[cl * 528 + h * 64 + 4 * quad]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = r0 + 4 * u + (lane >> 4);
+                if (r < n_rows) {
+                    const int cl = r / G, h = r - cl * G;
+                    const int64_t row = ((int64_t)bb * prm.Hq + g * G + h) * prm.n_splits + chunk0 + cl;
+                    __builtin_nontemporal_store(x[u], reinterpret_cast<f32x4 *>(prm.ws_acc + row * 64 + 4 * quad));
+                }
+            }
+        }
+        for (int r = lane; r < n_rows; r += 64) {      // (m, l) pairs: one lane per (chunk, head)
+            const int cl = r / G, h = r - cl * G;
+            const int64_t row = ((int64_t)bb * prm.Hq + g * G + h) * prm.n_splits + chunk0 + cl;
+            __builtin_nontemporal_store(lds[cl * 528 + 512 + h], prm.ws_ml + row * 2);
+            __builtin_nontemporal_store(lds[cl * 528 + 520 + h], prm.ws_ml + row * 2 + 1);
+        }
+        __syncthreads();                               // the records are free again
+    };
+
+    bool first_run = true;
+    int remaining = (int)(c_end - c_begin);
+    while (remaining > 0) {
+        const int L = prm.seq_lens[b];
+        const int nb = chunks_of(L);
+        if (c >= nb) {                                 // sequence used up (or without chunks): next one
+            if (++b >= prm.B) break;                   // cannot happen while chunks remain; keeps the loop finite
+            c = 0;
+            continue;
+        }
+        const int c_first = c;
+        const int c_last = c + min(nb - c, remaining);
+        remaining -= c_last - c_first;
+        c = c_last;
+
+        // ---- one run: chunks [c_first, c_last) of sequence b
+        const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
+        const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
+        const int a0 = lo & ~63;
+        const int a0_step = a0 >> 6;
+        const int j0 = max(lo, a0 + c_first * split);
+        const int j1 = (int)min((int64_t)L, (int64_t)a0 + (int64_t)c_last * split);
+        const int s0 = j0 >> 6, s1 = (j1 + 63) >> 6;   // s0 < s1: every chunk of the list holds a position
+        const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
+        const bool use_early = first_run && b == spec_b && c_first == spec_c;
+        first_run = false;
+
+        // Q^T operand: column n holds head n%8 of the group (zero beyond the group size)
+        bf16x8 qb[2];
+        {
+            u32x4 q0 = {0, 0, 0, 0}, q1 = {0, 0, 0, 0};
+            if (head < G) {
+                const uint16_t *qrow = prm.q + ((int64_t)b * prm.Hq + qh) * 64 + 16 * kb;
+                q0 = *reinterpret_cast<const u32x4 *>(qrow);
+                q1 = *reinterpret_cast<const u32x4 *>(qrow + 8);
+            }
+            qb[0] = __builtin_bit_cast(bf16x8, q0);
+            qb[1] = __builtin_bit_cast(bf16x8, q1);
+        }
+
+        int parked = 0, park_chunk0 = c_first;
+        KTile<EB> kt;
+        VTile<EB> vt;
+        // Steps are walked in groups whose page ids sit in two registers; inside a group the K buffer is
+        // refilled right after QK^T has consumed it and the V buffer right after PV, unconditionally; the
+        // group's last step is peeled so that no load is conditional (see pz_attn.hip).
+        for (int gs = s0; gs < s1; gs += GROUP) {
+            const int ge = min(gs + GROUP, s1);
+            const int pbase = gs * NPS;
+            int ids0, ids1;
+            if (use_early && gs == s0) {               // s0 == spec_c * steps_per_chunk here (window == 0)
+                const int last = pmax - pbase;         // >= 0: the group holds an attended position
+                const int fix0 = __shfl(early0, min(last, 63));
+                const int fix1 = __shfl(early1, min(max(last - 64, 0), 63));
+                ids0 = lane <= last ? early0 : fix0;
+                ids1 = last < 64 ? fix0 : (lane + 64 <= last ? early1 : fix1);
+            } else {
+                ids0 = bt[min(max(pbase + lane, pmin), pmax)];
+                ids1 = bt[min(max(pbase + 64 + lane, pmin), pmax)];
+            }
+            auto page_id = [&](int idx) -> int {       // idx: page index relative to pbase, < 128
+                if constexpr (NPS == 1) {
+                    const int a = __builtin_amdgcn_readlane(ids0, idx & 63);
+                    const int cc = __builtin_amdgcn_readlane(ids1, idx & 63);
+                    return idx < 64 ? a : cc;
+                } else {
+                    const int a = __shfl(ids0, idx & 63), cc = __shfl(ids1, idx & 63);
+                    return idx < 64 ? a : cc;
+                }
+            };
+            auto k_page = [&](int s) -> const uint8_t * {
+                return kbase + (int64_t)page_id(s * NPS + geom.kslot - pbase) * page_bytes;
+            };
+            auto v_page = [&](int s) -> const uint8_t * {
+                return vbase + (int64_t)page_id(s * NPS + geom.vslot - pbase) * page_bytes;
+            };
+            auto step = [&](int s, bool prefetch) {
+                const int base = s << 6;
+                const bool full = base >= j0 && base + 64 <= j1;
+                const unsigned valid = full ? 0xffffu : valid_mask(base + 16 * kb, j0, j1);
+                f32x4 sacc[4];
+                qk_step<EB>(kt, qb, sacc);
+                if (prefetch) load_k<P, EB>(kt, k_page(s + 1), geom.koff);
+                if (!full) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
+                }
+                u32x4 pw[2];
+                softmax_step(sacc, sc, lo_mask, st, pw);
+                if (!full) mask_v<EB>(vt, valid);
+                pv_step<EB>(vt, pw, st);
+                if (prefetch) load_v<P, EB>(vt, v_page(s + 1), geom.voff);
+                // a chunk ends after this step -> park its partial
+                if ((s + 1 - a0_step) % steps_per_chunk == 0 || s + 1 == s1) {
+                    park(parked);
+                    ++parked;
+                }
+            };
+            load_k<P, EB>(kt, k_page(gs), geom.koff);
+            load_v<P, EB>(vt, v_page(gs), geom.voff);
+            // Fused append (see pz_attn.hip): the run that reaches position L - 1 writes the newest
+            // token's K/V (lane = channel) after its first loads are on their way.
+            if (gs == s0 && prm.k_new != nullptr && j1 == L) {
+                const int pos = L - 1;
+                const int64_t page = bt[pos / P];
+                const int off = pos % P;
+                const int gc = g >> prm.head_shift;
+                const int64_t src = ((int64_t)b * prm.cache_heads + gc) * 64 + lane;
+                const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
+                uint8_t *kd = prm.k + (((page * prm.cache_heads + gc) * P + off) * 64 + lane) * EB;
+                uint8_t *vd = prm.v + (((page * prm.cache_heads + gc) * 64 + lane) * P + off) * EB;
+                if constexpr (EB == 1) {
+                    *kd = (uint8_t)quant_one(kb16, prm.k_scale);
+                    *vd = (uint8_t)quant_one(vb16, prm.v_scale);
+                } else {
+                    *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
+                    *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
+                }
+                if (((L - 1) >> 6) == gs) {            // the step just loaded holds position L - 1
+                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+                    load_k<P, EB>(kt, k_page(gs), geom.koff);
+                    load_v<P, EB>(vt, v_page(gs), geom.voff);
+                }
+            }
+            for (int s = gs; s + 1 < ge; ++s) {
+                step(s, true);
+                if (__builtin_expect(parked == kPark, 0)) {   // records full in the middle of a run: write them out
+                    write_out(b, park_chunk0, parked);
+                    park_chunk0 += parked;
+                    parked = 0;
+                }
+            }
+            step(ge - 1, false);
+            if (parked == kPark || ge == s1) {
+                if (parked > 0) write_out(b, park_chunk0, parked);
+                park_chunk0 += parked;
+                parked = 0;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+namespace pz {
+
+// Workgroups of decode_attn_balanced_kernel that fit the device at once (one wave each): the
+// partition wants the whole grid resident, so the grid is never larger than this.
+static int balanced_slots(int page_size, int elem_bytes) {
+    static int cached[2][3] = {{0, 0, 0}, {0, 0, 0}};
+    const int pi = page_size == 64 ? 0 : (page_size == 32 ? 1 : 2), ei = elem_bytes - 1;
+    if (cached[ei][pi] > 0) return cached[ei][pi];
+    int per_cu = 0, dev = 0, cus = 0;
+    const size_t lds_bytes = kPark * 528 * sizeof(float);
+    hipError_t e;
+#define PZ_OCC(PP, EE) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_balanced_kernel<PP, EE>, 64, lds_bytes)
+    if (elem_bytes == 1) {
+        if (page_size == 64) PZ_OCC(64, 1);
+        else if (page_size == 32) PZ_OCC(32, 1);
+        else PZ_OCC(16, 1);
+    } else {
+        if (page_size == 64) PZ_OCC(64, 2);
+        else if (page_size == 32) PZ_OCC(32, 2);
+        else PZ_OCC(16, 2);
+    }
+#undef PZ_OCC
+    if (e != hipSuccess || per_cu <= 0) per_cu = 8;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
+    cached[ei][pi] = per_cu * cus;
+    return cached[ei][pi];
+}
+
+hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream) {
+    // workgroups per KV head: at most one per chunk that can exist, and never more than fit the device
+    // at once
+    const int64_t cap_chunks = (int64_t)prm.B * prm.n_splits;
+    int64_t bph = cap_chunks;                          // the kernel decides how many of them take a share
+    const int64_t slots = balanced_slots(page_size, elem_bytes) / prm.Hkv;
+    if (bph > slots) bph = slots;
+    if (bph < 1) bph = 1;
+    const dim3 grid((unsigned)(bph * prm.Hkv)), block(64);
+    const size_t lds_bytes = kPark * 528 * sizeof(float);
+#define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, lds_bytes, stream, prm)
+    if (elem_bytes == 1) {
+        if (page_size == 64) PZ_LAUNCH(64, 1);
+        else if (page_size == 32) PZ_LAUNCH(32, 1);
+        else PZ_LAUNCH(16, 1);
+    } else {
+        if (page_size == 64) PZ_LAUNCH(64, 2);
+        else if (page_size == 32) PZ_LAUNCH(32, 2);
+        else PZ_LAUNCH(16, 2);
+    }
+#undef PZ_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace pz

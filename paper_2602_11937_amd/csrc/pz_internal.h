@@ -30,6 +30,8 @@ struct AttnParams {
     float v_scale;
 };
 
+hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream);
+
 struct ReduceParams {
     const float *ws_acc;
     const float *ws_ml;

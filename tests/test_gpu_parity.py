@@ -307,11 +307,46 @@ def test_split_count_invariance():
 
 # ------------------------------------------------------------------ launch shapes
 
-@pytest.mark.parametrize("waves,cpg", [(1, 1), (1, 2), (1, 3), (1, 8), (2, 1), (4, 1), (8, 1)])
-def test_every_launch_shape_gives_the_same_answer(waves, cpg, monkeypatch):
-    """Waves per workgroup and chunks per workgroup are launch heuristics; force each shape."""
+@pytest.mark.parametrize("B,max_len,split", [(150, 400, 64), (70, 3000, 256), (64, 900, 128), (65, 130, 64),
+                                             (300, 64, 64), (5, 20000, 1024)])
+def test_balanced_partition_over_many_ragged_sequences(B, max_len, split, monkeypatch):
+    """Full-attention split-K deals the chunks of the whole batch out evenly: batches beyond one
+    64-lane strip of lengths, shares that span several sequences, sequences without a token, and
+    (forced by one wave per workgroup) totals far below the number of workgroups."""
+    monkeypatch.setenv("PZ_ATTN_WAVES", "1")
+    rng = np.random.default_rng(B + split)
+    lens = rng.integers(0, max_len + 1, size=B)
+    lens[rng.integers(0, B, size=max(1, B // 10))] = 0
+    lens[-1] = max_len
+    case = wl.make_case("bal", B=B, Hq=8, Hkv=2, d=64, P=64, seq_lens=lens.tolist(), seed=B)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    want = oracle_attn(case, kc, vc, accum="f64")
+    got, acc, ml = gpu_attn(case, cache, split_tokens=split, return_ws=True)
+    assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL
+    assert np.all(got[lens == 0] == 0)
+    # every chunk that holds a position was written exactly where the merge expects it, no other row was
+    for b in range(B):
+        n_b = -(-int(lens[b]) // split)
+        assert np.all(np.isfinite(ml[b, :, :n_b])) and np.all(np.isnan(ml[b, :, n_b:]))
+    oacc, oml = oracle.decode_attn_partials(kc, vc, case.P, case.q, case.block_table, case.seq_lens, case.sm_scale,
+                                            case.k_scale, 0, split, ml.shape[2], accum="f64", nthreads=8)
+    live = np.isfinite(ml[..., 0])
+    assert np.array_equal(live, oml[..., 0] > -np.inf)
+    assert np.allclose(ml[..., 0][live], oml[..., 0][live], atol=2e-3)
+    avg_g = acc[live] / ml[..., 1][live][:, None]
+    avg_o = oacc[live] / oml[..., 1][live][:, None]
+    assert rel_err(avg_g, avg_o) <= TOL
+
+
+@pytest.mark.parametrize("waves,cpg,balanced", [(1, 1, 0), (1, 2, 0), (1, 3, 0), (1, 8, 0), (1, 1, 1), (2, 1, 1),
+                                                (4, 1, 1), (8, 1, 1)])
+def test_every_launch_shape_gives_the_same_answer(waves, cpg, balanced, monkeypatch):
+    """Waves per workgroup, chunks per workgroup and the balanced partition of full-attention split-K
+    are launch heuristics; force each shape."""
     monkeypatch.setenv("PZ_ATTN_WAVES", str(waves))
     monkeypatch.setenv("PZ_ATTN_CHUNKS_PER_GROUP", str(cpg))
+    monkeypatch.setenv("PZ_ATTN_BALANCED", str(balanced))
     case = wl.make_case("l", B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[2000, 130, 700], seed=21)
     cache = gpu_cache(case)
     kc, vc = oracle_cache(case)
