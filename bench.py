@@ -31,7 +31,7 @@ import numpy as np  # noqa: E402
 
 # HBM bytes per decode_attn launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/decode_step_cfg3_fp8_hbm_traffic.txt:
 # counters scaled by what they read for a plain 768 MiB copy); only measured for the default cfg3 launch.
-MEASURED_TRAFFIC_BYTES = {"cfg3": 1091920643}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 1092466110}
 
 METRIC = "decode-attention GB/s (% of HBM peak) + attn tokens/s, B=16 ctx=64K FP8 KV"
 HBM_PEAK_GBPS = 8000.0
@@ -361,7 +361,7 @@ def run_cfg5(args, pz, wl, torch):
         "config": {"workload": text, "batch": B, "layers": by_type},
         "attn_tokens_per_s": B / (ms_step * 1e-3),
         "pct_hbm_peak": 100.0 * step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel<64,1> (the 10 full-attention layers)",
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_balanced_kernel<64,1> (the 10 full-attention layers)",
                      "achieved": full_bytes / (kern_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": full_bytes / (kern_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, "kernel_us_avg": kern_avg * 1e3,
                      "ms_per_step_with_events": ms_ev, "algorithmic_bytes_per_launch": full_bytes, "traffic": None},
@@ -618,7 +618,8 @@ def main():
                    "cache_instances_rotated": len(layers)},
         "attn_tokens_per_s": B / (ms_step * 1e-3),
         "pct_hbm_peak": 100.0 * step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel<64,1>",
+        "roofline": {"bound": "hbm", "kernel": ("decode_attn_balanced_kernel<64,1>" if spec["window"] == 0 and
+                                                spec["split_tokens"] > 0 else "decode_attn_kernel<64,1>"),
                      "achieved": attn_bytes / (kern_avg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": attn_bytes / (kern_avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "kernel_us_avg": kern_avg_ms * 1e3, "kernel_us_std": float(kern_ms.std() * 1e3),
