@@ -14,7 +14,7 @@
 // chunks, and the few workgroups that differ have LESS work, so nothing is left over at the end.
 // A share may span several sequences; each run of chunks inside one sequence is streamed with
 // the register pipeline of pz_attn.hip, its partials parked in LDS and written out when the run
-// ends (or when 4 are parked).  The partition is a pure function of the lengths: no queue, no
+// ends (or when the LDS records are full).  The partition is a pure function of the lengths: no queue, no
 // atomics, nothing to wait for.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -26,9 +26,9 @@
 
 namespace {
 
-// Partials parked in LDS before a write-out.  A share holds more chunks than this only when the
-// batch has more chunks than 6 x the workgroups the device holds at once.
-constexpr int kPark = 6;
+// Partials parked in LDS before a write-out (4 records of 2112 bytes leave room for four workgroups
+// per SIMD).  A share with more chunks is streamed in groups of at most this many.
+constexpr int kPark = 4;
 
 // Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS traffic): four shifted adds
 // inside every row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then
@@ -55,11 +55,13 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     const int n = lane & 15, kb = lane >> 4;
     const int head = n & 7;
     const int G = prm.G;
-    // share index fastest: neighbouring workgroups (which the dispatcher deals to different XCDs) work
-    // on the same KV head, so every XCD streams all heads, as it does in decode_attn_kernel
+    // Workgroup t works on share t / Hkv of KV head (t + t / Hkv) % Hkv.  The active shares are the lowest
+    // ones, so the workgroups that stream are the first of the grid and are placed like a launch of
+    // just that many (the idle rest is dispatched after them and leaves at once); the rotation makes
+    // every XCD, which receives every eighth workgroup, stream all KV heads.
     const int bph = gridDim.x / prm.Hkv;               // workgroups per KV head
-    const int i_blk = blockIdx.x % bph;
-    const int g = blockIdx.x / bph;
+    const int i_blk = blockIdx.x / prm.Hkv;
+    const int g = (blockIdx.x + i_blk) % prm.Hkv;
     const int split = prm.split_tokens;
     const int steps_per_chunk = split >> 6;
 
@@ -71,62 +73,80 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     };
     // the share of this workgroup out of `tot` chunks: [begin, end) of the list, or nothing.  The host
     // keeps batch * n_kv_heads * n_splits below 2^31, so 32-bit arithmetic is enough.
-    auto share = [&](unsigned tot, unsigned &begin, unsigned &end) -> bool {
-        if (tot == 0) return false;
-        // 4 chunks per workgroup while that still gives 2048 waves, fewer for small jobs
-        const unsigned want = min(4u, max(1u, tot * (unsigned)prm.Hkv / 2048u));
-        const unsigned cap = min((unsigned)bph, (tot + want - 1) / want);
-        const unsigned k = (tot + cap - 1) / cap;      // chunks of the largest shares
-        const unsigned n_act = (tot + k - 1) / k;
+    auto pick = [&](unsigned n_act, unsigned q, unsigned r, unsigned &begin, unsigned &end) -> bool {
         const unsigned i = (unsigned)i_blk;
         if (i >= n_act) return false;
-        const unsigned q = tot / n_act, r = tot - q * n_act;   // the first r shares hold q + 1 = k chunks
-        begin = i * q + min(i, r);
+        begin = i * q + min(i, r);                     // the first r shares hold q + 1 chunks
         end = begin + q + (i < r ? 1u : 0u);
         return true;
+    };
+    auto share = [&](unsigned tot, unsigned &begin, unsigned &end) -> bool {
+        if (tot == 0) return false;
+        unsigned n_act, q, r;
+        pz::balanced_plan(tot, (unsigned)prm.Hkv, (unsigned)bph, &n_act, &q, &r);
+        return pick(n_act, q, r, begin, end);
     };
 
     // Before the lengths are known: if every sequence had the longest length this workgroup would
     // start at (spec_b, spec_c); the block-table entries of that place are fetched beside the
     // lengths and used when the guess holds (it always does for a uniform batch).
+    const unsigned tot_full = (unsigned)prm.B * (unsigned)prm.n_splits;
+    unsigned spec_begin = 0, spec_end = 0;
+    const bool spec_active = pick(prm.full_n_act, prm.full_q, prm.full_r, spec_begin, spec_end);
     int spec_b = -1, spec_c = 0, early0 = 0, early1 = 0;
-    if (prm.window == 0) {
-        unsigned sb, se;
-        if (share((unsigned)prm.B * (unsigned)prm.n_splits, sb, se)) {
-            spec_b = (int)(sb / (unsigned)prm.n_splits);
-            spec_c = (int)(sb - (unsigned)spec_b * (unsigned)prm.n_splits);
-            const int32_t *row = prm.block_table + (int64_t)spec_b * prm.max_pages;
-            const int p0 = spec_c * steps_per_chunk * NPS;
-            early0 = row[min(p0 + lane, prm.max_pages - 1)];
-            early1 = row[min(p0 + 64 + lane, prm.max_pages - 1)];
-        }
+    if (spec_active && prm.window == 0) {
+        spec_b = (int)(spec_begin / (unsigned)prm.n_splits);
+        spec_c = (int)(spec_begin - (unsigned)spec_b * (unsigned)prm.n_splits);
+        const int32_t *row = prm.block_table + (int64_t)spec_b * prm.max_pages;
+        const int p0 = spec_c * steps_per_chunk * NPS;
+        early0 = row[min(p0 + lane, prm.max_pages - 1)];
+        early1 = row[min(p0 + 64 + lane, prm.max_pages - 1)];
     }
 
-    // chunk count of the batch and, for a batch of at most 64 sequences, its prefix sums
+    // chunk count of the batch and, for the first 64 sequences, the lengths and prefix sums
     unsigned tot = 0;
-    int nn0 = 0, incl0 = 0;
-    for (int base = 0; base < prm.B; base += 64) {
+    int len0 = 0, nn0 = 0, incl0 = 0;
+    bool found = false;                                // (b, c, L_first) already known
+    int b = 0, c = 0, L_first = 0;
+    if (prm.B <= 64) {
+        // one strip of lengths, all equal and full: the guess above is the answer, no sums needed
+        len0 = (lane < prm.B) ? prm.seq_lens[lane] : 0;
+        const int L0 = __builtin_amdgcn_readfirstlane(len0);
+        if (__ballot(lane < prm.B && len0 != L0) == 0 && chunks_of(L0) == prm.n_splits && spec_b >= 0) {
+            if (!spec_active) return;
+            found = true;
+            tot = tot_full;
+            b = spec_b;
+            c = spec_c;
+            L_first = L0;
+        }
+    }
+    for (int base = 0; base < prm.B && !found; base += 64) {
         const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
         const int nn = chunks_of(L);
         const int incl = wave_inclusive_scan_int(nn);
         if (base == 0) {
+            len0 = L;
             nn0 = nn;
             incl0 = incl;
         }
         tot += __builtin_amdgcn_readlane(incl, 63);     // uniform: stays scalar
     }
-    unsigned c_begin, c_end;
-    if (!share(tot, c_begin, c_end)) return;
+    unsigned c_begin = spec_begin, c_end = spec_end;
+    if (tot != tot_full) {
+        if (!share(tot, c_begin, c_end)) return;
+    } else if (!spec_active) {
+        return;
+    }
 
-    // the sequence that holds list entry c_begin, and the chunk inside it
-    int b = 0, c = 0;
-    {
+    // the sequence that holds list entry c_begin, the chunk inside it, and the sequence's length
+    if (!found) {
         unsigned run = 0;
         for (int base = 0; base < prm.B; base += 64) {
-            int nn = nn0, incl = incl0;
+            int len = len0, nn = nn0, incl = incl0;
             if (base > 0) {
-                const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
-                nn = chunks_of(L);
+                len = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
+                nn = chunks_of(len);
                 incl = wave_inclusive_scan_int(nn);
             }
             const uint64_t past = __ballot(run + (unsigned)incl > c_begin);
@@ -134,6 +154,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 const int l0 = __builtin_ctzll(past);
                 b = base + l0;
                 c = (int)(c_begin - (run + __builtin_amdgcn_readlane(incl, l0) - __builtin_amdgcn_readlane(nn, l0)));
+                L_first = __builtin_amdgcn_readlane(len, l0);
                 break;
             }
             run += __builtin_amdgcn_readlane(incl, 63);
@@ -210,11 +231,12 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
 
     bool first_run = true;
     int remaining = (int)(c_end - c_begin);
+    int L = L_first;                                   // length of sequence b
     while (remaining > 0) {
-        const int L = prm.seq_lens[b];
         const int nb = chunks_of(L);
         if (c >= nb) {                                 // sequence used up (or without chunks): next one
             if (++b >= prm.B) break;                   // cannot happen while chunks remain; keeps the loop finite
+            L = prm.seq_lens[b];
             c = 0;
             continue;
         }
@@ -254,8 +276,11 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         // Steps are walked in groups whose page ids sit in two registers; inside a group the K buffer is
         // refilled right after QK^T has consumed it and the V buffer right after PV, unconditionally; the
         // group's last step is peeled so that no load is conditional (see pz_attn.hip).
-        for (int gs = s0; gs < s1; gs += GROUP) {
-            const int ge = min(gs + GROUP, s1);
+        for (int gs = s0; gs < s1;) {
+            // a group also ends where the LDS records run out, so that partials are written out only
+            // between groups, where the pipeline is drained anyway
+            const int ge_park = a0_step + ((gs - a0_step) / steps_per_chunk + (kPark - parked)) * steps_per_chunk;
+            const int ge = min(min(gs + GROUP, s1), ge_park);
             const int pbase = gs * NPS;
             int ids0, ids1;
             if (use_early && gs == s0) {               // s0 == spec_c * steps_per_chunk here (window == 0)
@@ -335,20 +360,14 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                     load_v<P, EB>(vt, v_page(gs), geom.voff);
                 }
             }
-            for (int s = gs; s + 1 < ge; ++s) {
-                step(s, true);
-                if (__builtin_expect(parked == kPark, 0)) {   // records full in the middle of a run: write them out
-                    write_out(b, park_chunk0, parked);
-                    park_chunk0 += parked;
-                    parked = 0;
-                }
-            }
+            for (int s = gs; s + 1 < ge; ++s) step(s, true);
             step(ge - 1, false);
             if (parked == kPark || ge == s1) {
                 if (parked > 0) write_out(b, park_chunk0, parked);
                 park_chunk0 += parked;
                 parked = 0;
             }
+            gs = ge;
         }
     }
 }
@@ -385,14 +404,15 @@ static int balanced_slots(int page_size, int elem_bytes) {
     return cached[ei][pi];
 }
 
-hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream) {
-    // workgroups per KV head: at most one per chunk that can exist, and never more than fit the device
-    // at once
-    const int64_t cap_chunks = (int64_t)prm.B * prm.n_splits;
-    int64_t bph = cap_chunks;                          // the kernel decides how many of them take a share
-    const int64_t slots = balanced_slots(page_size, elem_bytes) / prm.Hkv;
-    if (bph > slots) bph = slots;
+hipError_t launch_decode_attn_balanced(const AttnParams &prm_in, int page_size, int elem_bytes, hipStream_t stream) {
+    // workgroups per KV head: as many as the kernel activates when every sequence has the longest length
+    // (it never activates more), and never more than fit the device at once
+    AttnParams prm = prm_in;
+    const unsigned cap_chunks = (unsigned)prm.B * (unsigned)prm.n_splits;
+    unsigned bph = (unsigned)(balanced_slots(page_size, elem_bytes) / prm.Hkv);
     if (bph < 1) bph = 1;
+    balanced_plan(cap_chunks, (unsigned)prm.Hkv, bph, &prm.full_n_act, &prm.full_q, &prm.full_r);
+    bph = prm.full_n_act;
     const dim3 grid((unsigned)(bph * prm.Hkv)), block(64);
     const size_t lds_bytes = kPark * 528 * sizeof(float);
 #define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, lds_bytes, stream, prm)

@@ -26,11 +26,30 @@ struct AttnParams {
     int32_t cache_heads, head_shift;    // KV heads of the cache; virtual head g reads cache head g >> head_shift
     int32_t window, split_tokens, n_splits, out_dtype;
     int32_t chunks_per_group;    // consecutive split-K chunks walked by one workgroup (1 unless it is one wave)
+    // balanced kernel: the partition of a batch whose sequences all have n_splits chunks, worked out on
+    // the host (n_act shares; the first r hold q + 1 chunks, the others q)
+    uint32_t full_n_act, full_q, full_r;
     float sc;                    // sm_scale * k_scale * log2(e)
     float v_scale;
 };
 
 hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream);
+
+// Balanced partition of `tot` chunks of one KV head over at most `bph` workgroups: n_act shares, the
+// first r of q + 1 chunks, the others of q.  About 4 chunks per share while that still gives 2048
+// waves over all heads, fewer for small jobs, more when the grid is capped; with k = q + 1 (or q when
+// r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ are the smaller ones.
+__host__ __device__ inline void balanced_plan(unsigned tot, unsigned n_heads, unsigned bph, unsigned *n_act,
+                                              unsigned *q, unsigned *r) {
+    unsigned want = tot * n_heads / 2048u;
+    want = want < 1u ? 1u : (want > 4u ? 4u : want);
+    unsigned cap = (tot + want - 1u) / want;
+    if (cap > bph) cap = bph;
+    const unsigned k = (tot + cap - 1u) / cap;
+    *n_act = (tot + k - 1u) / k;
+    *q = tot / *n_act;
+    *r = tot - *q * *n_act;
+}
 
 struct ReduceParams {
     const float *ws_acc;
