@@ -339,6 +339,22 @@ def test_balanced_partition_over_many_ragged_sequences(B, max_len, split, monkey
     assert rel_err(avg_g, avg_o) <= TOL
 
 
+def test_balanced_partition_degenerate_batches(monkeypatch):
+    """No chunk at all (every sequence empty), a single sequence, and one chunk for the whole batch."""
+    monkeypatch.setenv("PZ_ATTN_WAVES", "1")
+    for lens, split in (([0, 0, 0], 64), ([777], 64), ([5], 1024), ([0, 3, 0, 0], 128), ([64] * 70, 64)):
+        case = wl.make_case("deg", B=len(lens), Hq=8, Hkv=2, d=64, P=16, seq_lens=lens, seed=len(lens))
+        cache = gpu_cache(case)
+        kc, vc = oracle_cache(case)
+        want = oracle_attn(case, kc, vc, accum="f64")
+        got = gpu_attn(case, cache, split_tokens=split, n_splits=max(1, -(-max(lens) // split)))
+        assert not np.any(np.isnan(got))
+        if max(lens) == 0:
+            assert np.all(got == 0)
+        else:
+            assert rel_err(got, want) <= TOL
+
+
 @pytest.mark.parametrize("waves,cpg,balanced", [(1, 1, 0), (1, 2, 0), (1, 3, 0), (1, 8, 0), (1, 1, 1), (2, 1, 1),
                                                 (4, 1, 1), (8, 1, 1)])
 def test_every_launch_shape_gives_the_same_answer(waves, cpg, balanced, monkeypatch):
