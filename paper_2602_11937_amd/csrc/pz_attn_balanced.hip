@@ -9,13 +9,13 @@
 // every workgroup (one wave64) first reads all sequence lengths, counts the chunks that exist,
 //     n_b = min(n_splits, ceil((L_b - a_b) / split_tokens)),   tot = sum_b n_b,
 // and takes an equal share of the list (b, chunk) in sequence order for its KV head: with
-// k = ceil(tot / blocks_per_head) chunks in the largest share, n_act = ceil(tot / k) workgroups
-// are active and workgroup i owns list entries [i tot / n_act, (i+1) tot / n_act) -- k or k-1
-// chunks, and the few workgroups that differ have LESS work, so nothing is left over at the end.
+// k = ceil(tot / workgroups_per_head) chunks in the largest share, n_act = ceil(tot / k) workgroups
+// are active; the first tot mod n_act shares hold k chunks and the others k - 1, so the shares
+// that differ have LESS work and nothing is left over at the end (balanced_plan, pz_internal.h).
 // A share may span several sequences; each run of chunks inside one sequence is streamed with
 // the register pipeline of pz_attn.hip, its partials parked in LDS and written out when the run
-// ends (or when the LDS records are full).  The partition is a pure function of the lengths: no queue, no
-// atomics, nothing to wait for.
+// ends or, between two groups of loads, when the LDS records are full.  The partition is a pure
+// function of the lengths: no queue, no atomics, nothing to wait for.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -43,8 +43,9 @@ __device__ __forceinline__ int wave_inclusive_scan_int(int x) {
     return x;
 }
 
-// Three waves per SIMD is the register budget: with four the compiler spills in the run set-up, and the
-// partition never needs more than the workgroups that stream well together (two to three per SIMD).
+// The stated budget is three waves per SIMD (170 registers); the kernel needs 126 for FP8 caches with
+// 64-token pages and then runs four per SIMD.  Asking for four makes the compiler schedule for
+// register pressure and spill in the run set-up, which cost 10 %.
 template <int P, int EB>
 __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
