@@ -23,6 +23,13 @@
  *     n_kv_heads with group size n_q_heads / n_kv_heads <= 8, or an even group size <= 16
  *     (the attention kernels then read each KV head twice, once per half of its group).
  *
+ *   - Launch shapes are chosen by the library.  Three environment variables override the choice,
+ *     for tests and measurements only (results are the same for every shape):
+ *       PZ_ATTN_WAVES=1|2|4|8            waves per workgroup of the decode-attention kernel
+ *       PZ_ATTN_CHUNKS_PER_GROUP=n       consecutive split-K chunks walked by a one-wave workgroup
+ *       PZ_ATTN_BALANCED=0               full-attention split-K on the fixed (sequence, chunk group)
+ *                                        grid instead of the partition balanced over the batch
+ *
  * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
  * discuss paging):
  *     K : [num_pages][n_kv_heads][page_size][head_dim]     (a token's channels are contiguous)
