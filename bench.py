@@ -343,6 +343,7 @@ def run_cfg5(args, pz, wl, torch):
     model = Model(pz, wl, torch, pz.KV_FP8, keep_context_types=(128, 8192, 0) if args.cpu_seqs > 0 else ())
     log("built the 36 FP8 layer caches in %.1f s" % (time.perf_counter() - t0))
     ms_step, _ = time_model(torch, model, args.steps, args.warmup, events=False)
+    reps = [ms_step] + [time_model(torch, model, args.steps, 1, events=False)[0] for _ in range(3)]
     ms_ev, kern = time_model(torch, model, args.steps, args.warmup, events=True)
     step_bytes = float(sum(l.step_bytes(wl) for l in model.layers))
     full_bytes = float(np.mean([l.attn_bytes(wl) for l in model.full]))
@@ -361,6 +362,7 @@ def run_cfg5(args, pz, wl, torch):
         "config": {"workload": text, "batch": B, "layers": by_type},
         "attn_tokens_per_s": B / (ms_step * 1e-3),
         "pct_hbm_peak": 100.0 * step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "repetitions": {"n": len(reps), "ms_per_step_mean": float(np.mean(reps)), "ms_per_step_std": float(np.std(reps))},
         "roofline": {"bound": "hbm", "kernel": "decode_attn_balanced_kernel<64,1> (the 10 full-attention layers)",
                      "achieved": full_bytes / (kern_avg * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": full_bytes / (kern_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, "kernel_us_avg": kern_avg * 1e3,
@@ -602,6 +604,8 @@ def main():
                     keep_context=(r == 0 and args.cpu_seqs > 0)) for r in range(spec["instances"])]
     log("built %d FP8 cache instances in %.1f s" % (len(layers), time.perf_counter() - t_setup))
     ms_step, _ = time_steps(torch, layers, args.steps, args.warmup, events=False)
+    # three more timed regions of the same K steps: spread of the step time between repetitions
+    reps = [ms_step] + [time_steps(torch, layers, args.steps, 2, events=False)[0] for _ in range(3)]
     ms_step_ev, kern_ms = time_steps(torch, layers, args.steps, args.warmup, events=True)
     attn_bytes = float(np.mean([l.attn_bytes(wl) for l in layers]))
     step_bytes = float(np.mean([l.step_bytes(wl) for l in layers]))
@@ -618,6 +622,7 @@ def main():
                    "cache_instances_rotated": len(layers)},
         "attn_tokens_per_s": B / (ms_step * 1e-3),
         "pct_hbm_peak": 100.0 * step_bytes / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "repetitions": {"n": len(reps), "ms_per_step_mean": float(np.mean(reps)), "ms_per_step_std": float(np.std(reps))},
         "roofline": {"bound": "hbm", "kernel": ("decode_attn_balanced_kernel<64,1>" if spec["window"] == 0 and
                                                 spec["split_tokens"] > 0 else "decode_attn_kernel<64,1>"),
                      "achieved": attn_bytes / (kern_avg_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
