@@ -13,7 +13,10 @@ Prints ONE JSON line: metric / value (algorithmic GB/s of the whole step) / ms_p
 (the dominant kernel: algorithmic bytes per launch over its event-timed duration, against the 8 TB/s
 HBM peak, plus the HBM traffic measured with hardware counters), `cpu_baseline` (the CPU oracle timed
 on a bounded sample of the same workload, with a parity figure), `bf16_kv` (the same step on a BF16
-cache) and `tuned_split` (the same step with longer split-K chunks).
+cache), `repetitions` (spread of the step time over four timed regions), `fused_append` (the step with
+the append fused into the attention launch), `stream_read` (the box's plain streaming-read rate over
+the same cache bytes, measured in the same run), `hip_graph` (the step replayed from a HIP graph) and
+`tuned_split` (the same step with longer split-K chunks).
 """
 from __future__ import annotations
 
