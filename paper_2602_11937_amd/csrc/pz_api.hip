@@ -43,11 +43,12 @@ int round_down_pow2(int x) {
     return r;
 }
 
-// Launch shape.  The chip holds 1024 SIMDs; a wave streams best when it owns a long run of steps
-// (its start-up and its final store are latency it cannot hide), but ragged batches balance
-// best with many small items, so:
+// Launch shape of decode_attn_kernel.  The chip holds 1024 SIMDs; a wave streams best when it owns a
+// long run of steps (its start-up and its final store are latency it cannot hide), so:
 //   - with plenty of chunks, one-wave workgroups each walk several consecutive chunks
-//     (chunks_per_group, at most 4), keeping at least about two waves per SIMD;
+//     (chunks_per_group, at most 4), keeping at least about two waves per SIMD.  Full-attention
+//     split-K then goes to decode_attn_balanced_kernel instead, which deals the chunks out on the
+//     device; window layers and single-pass calls stay here;
 //   - with few (sequence, KV head, chunk) items, the steps of one item are dealt to several waves.
 void pick_shape(int batch, int n_kv_heads, int max_steps, int n_chunks, int *n_waves, int *chunks_per_group) {
     const long items = (long)batch * n_kv_heads * n_chunks;
