@@ -103,7 +103,7 @@ __device__ __forceinline__ void load_k(KTile<EB> &tile, const uint8_t *__restric
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int e = 0; e < EB; ++e)
-            tile.k[j * EB + e] = *reinterpret_cast<const u32x4 *>(kpage + koff + j * (4 * 64 * EB) + e * 16);
+            tile.k[j * EB + e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(kpage + koff + j * (4 * 64 * EB) + e * 16));
 }
 
 // V: channel tile c holds channels 16*c + t: +16 rows of P elements per c
@@ -113,7 +113,7 @@ __device__ __forceinline__ void load_v(VTile<EB> &tile, const uint8_t *__restric
     for (int c = 0; c < 4; ++c)
 #pragma unroll
         for (int e = 0; e < EB; ++e)
-            tile.v[c * EB + e] = *reinterpret_cast<const u32x4 *>(vpage + voff + c * (16 * P * EB) + e * 16);
+            tile.v[c * EB + e] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vpage + voff + c * (16 * P * EB) + e * 16));
 }
 
 // MFMA A operand of K tile j, channel half i (channels 16*kb + 8*i .. +7)
