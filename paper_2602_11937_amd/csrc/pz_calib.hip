@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void kv_amax_kernel(const uint16_t *__restrict
         const u32x4 *p = x8 + t * 512 + lane;
         u32x4 a[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a[u] = p[u * 64];
+        for (int u = 0; u < 8; ++u) a[u] = __builtin_nontemporal_load(p + u * 64);   // read once: streaming hint
 #pragma unroll
         for (int u = 0; u < 8; ++u)
 #pragma unroll
