@@ -316,7 +316,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 const unsigned valid = full ? 0xffffu : valid_mask(base + 16 * kb, j0, j1);
                 f32x4 sacc[4];
                 qk_step<EB>(kt, qb, sacc);
-                if (prefetch) load_k<P, EB, true>(kt, k_page(s + 1), geom.koff);
+                if (prefetch) load_k<P, EB, EB == 1>(kt, k_page(s + 1), geom.koff);
                 if (!full) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -328,15 +328,15 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 softmax_step(sacc, sc, lo_mask, st, pw);
                 if (!full) mask_v<EB>(vt, valid);
                 pv_step<EB>(vt, pw, st);
-                if (prefetch) load_v<P, EB, true>(vt, v_page(s + 1), geom.voff);
+                if (prefetch) load_v<P, EB, EB == 1>(vt, v_page(s + 1), geom.voff);
                 // a chunk ends after this step -> park its partial
                 if ((s + 1 - a0_step) % steps_per_chunk == 0 || s + 1 == s1) {
                     park(parked);
                     ++parked;
                 }
             };
-            load_k<P, EB, true>(kt, k_page(gs), geom.koff);
-            load_v<P, EB, true>(vt, v_page(gs), geom.voff);
+            load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
+            load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
             // Fused append (see pz_attn.hip): the run that reaches position L - 1 writes the newest
             // token's K/V (lane = channel) after its first loads are on their way.
             if (gs == s0 && prm.k_new != nullptr && j1 == L) {
@@ -357,8 +357,8 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 }
                 if (((L - 1) >> 6) == gs) {            // the step just loaded holds position L - 1
                     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-                    load_k<P, EB, true>(kt, k_page(gs), geom.koff);
-                    load_v<P, EB, true>(vt, v_page(gs), geom.voff);
+                    load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
+                    load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
                 }
             }
             for (int s = gs; s + 1 < ge; ++s) step(s, true);

@@ -97,8 +97,9 @@ __device__ __forceinline__ LaneGeom lane_geom(int lane) {
 }
 
 // STREAM: the bytes are used once (single-token decode), so they are loaded with the non-temporal
-// hint and do not displace anything in L2 -- worth 10 % of the decode kernel's time; the prefill
-// kernel, whose column tiles re-read K/V through L2, loads them normally.
+// hint and do not displace anything in L2 -- worth 10 % of the decode kernel's time.  It needs
+// every load instruction to cover whole cache lines: true for E4M3 tiles; a bf16 tile spreads each
+// line over two instructions, and the prefill kernel re-reads K/V through L2, so both load normally.
 template <bool STREAM>
 __device__ __forceinline__ u32x4 load16(const uint8_t *__restrict__ p) {
     if constexpr (STREAM) return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
