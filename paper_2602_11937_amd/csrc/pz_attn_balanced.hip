@@ -377,32 +377,31 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
 
 namespace pz {
 
-// Workgroups of decode_attn_balanced_kernel that fit the device at once (one wave each): the
-// partition wants the whole grid resident, so the grid is never larger than this.
-static int balanced_slots(int page_size, int elem_bytes) {
-    static int cached[2][3] = {{0, 0, 0}, {0, 0, 0}};
-    const int pi = page_size == 64 ? 0 : (page_size == 32 ? 1 : 2), ei = elem_bytes - 1;
-    if (cached[ei][pi] > 0) return cached[ei][pi];
+// Workgroups of decode_attn_balanced_kernel<P, EB> that fit the device at once (one wave each): the
+// partition wants the whole grid resident, so the grid is never larger than this.  Worked out once per
+// kernel variant (function-local static: initialised once, also with several host threads).
+template <int P, int EB>
+static int query_slots() {
     int per_cu = 0, dev = 0, cus = 0;
     const size_t lds_bytes = kPark * 528 * sizeof(float);
-    hipError_t e;
-#define PZ_OCC(PP, EE) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_balanced_kernel<PP, EE>, 64, lds_bytes)
-    if (elem_bytes == 1) {
-        if (page_size == 64) PZ_OCC(64, 1);
-        else if (page_size == 32) PZ_OCC(32, 1);
-        else PZ_OCC(16, 1);
-    } else {
-        if (page_size == 64) PZ_OCC(64, 2);
-        else if (page_size == 32) PZ_OCC(32, 2);
-        else PZ_OCC(16, 2);
-    }
-#undef PZ_OCC
-    if (e != hipSuccess || per_cu <= 0) per_cu = 8;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_balanced_kernel<P, EB>, 64, lds_bytes) !=
+            hipSuccess || per_cu <= 0)
+        per_cu = 8;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         cus = 256;
-    cached[ei][pi] = per_cu * cus;
-    return cached[ei][pi];
+    return per_cu * cus;
+}
+
+template <int P, int EB>
+static int slots_of() {
+    static const int slots = query_slots<P, EB>();
+    return slots;
+}
+
+static int balanced_slots(int page_size, int elem_bytes) {
+    if (elem_bytes == 1) return page_size == 64 ? slots_of<64, 1>() : (page_size == 32 ? slots_of<32, 1>() : slots_of<16, 1>());
+    return page_size == 64 ? slots_of<64, 2>() : (page_size == 32 ? slots_of<32, 2>() : slots_of<16, 2>());
 }
 
 hipError_t launch_decode_attn_balanced(const AttnParams &prm_in, int page_size, int elem_bytes, hipStream_t stream) {
