@@ -109,11 +109,15 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     int len0 = 0, nn0 = 0, incl0 = 0;
     bool found = false;                                // (b, c, L_first) already known
     int b = 0, c = 0, L_first = 0;
-    if (prm.B <= 64) {
-        // one strip of lengths, all equal and full: the guess above is the answer, no sums needed
-        len0 = (lane < prm.B) ? prm.seq_lens[lane] : 0;
-        const int L0 = __builtin_amdgcn_readfirstlane(len0);
-        if (__ballot(lane < prm.B && len0 != L0) == 0 && chunks_of(L0) == prm.n_splits && spec_b >= 0) {
+    {
+        // all lengths equal and full: the guess above is the answer, no sums needed
+        const int L0 = prm.seq_lens[0];
+        bool uniform = spec_b >= 0 && chunks_of(L0) == prm.n_splits;
+        for (int base = 0; base < prm.B && uniform; base += 64) {
+            const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : L0;
+            uniform = __ballot(L != L0) == 0;
+        }
+        if (uniform) {
             if (!spec_active) return;
             found = true;
             tot = tot_full;
