@@ -38,6 +38,8 @@ MEASURED_TRAFFIC_BYTES = {"cfg3": 1092826285}
 
 METRIC = "decode-attention GB/s (% of HBM peak) + attn tokens/s, B=16 ctx=64K FP8 KV"
 HBM_PEAK_GBPS = 8000.0
+CFG5_SPLIT = 8192      # split-K chunk length of cfg5's full and window-8192 layers (the configuration names none;
+                       # 8192 measured best: 1024 4.16 ms, 2048 4.11, 4096 3.90, 8192 3.85, 16384 4.11)
 
 WORKLOADS = {
     # name: (B, seq_lens spec, window, split_tokens, outlier_frac, seed, instances, description)
@@ -61,10 +63,10 @@ WORKLOADS = {
     "diag_b16_ragged": dict(B=16, L=(1024, 131072), window=0, split_tokens=1024, outlier_frac=0.0, seed=5, instances=4,
                             text="diagnostic: batch 16, ragged contexts U[1024,131072], split-K 1024"),
     # single layers of the heterogeneous step (cfg5), for tests and tuning
-    "cfg5_full": dict(B=32, L=(1024, 131072), window=0, split_tokens=1024, outlier_frac=0.0, seed=5, instances=3,
-                      bounded=True, text="cfg5 full-attention layer: batch 32, ragged contexts U[1024,131072], split-K 1024"),
-    "cfg5_w8192": dict(B=32, L=(1024, 131072), window=8192, split_tokens=1024, outlier_frac=0.0, seed=5, instances=3,
-                       bounded=True, text="cfg5 window-8192 layer: batch 32, ragged contexts U[1024,131072], split-K 1024"),
+    "cfg5_full": dict(B=32, L=(1024, 131072), window=0, split_tokens=CFG5_SPLIT, outlier_frac=0.0, seed=5, instances=3,
+                      bounded=True, text="cfg5 full-attention layer: batch 32, ragged contexts U[1024,131072], split-K %d" % CFG5_SPLIT),
+    "cfg5_w8192": dict(B=32, L=(1024, 131072), window=8192, split_tokens=CFG5_SPLIT, outlier_frac=0.0, seed=5, instances=3,
+                       bounded=True, text="cfg5 window-8192 layer: batch 32, ragged contexts U[1024,131072], split-K %d" % CFG5_SPLIT),
     "cfg5_w128": dict(B=32, L=(1024, 131072), window=128, split_tokens=0, outlier_frac=0.0, seed=5, instances=3,
                       bounded=True, text="cfg5 window-128 layer: batch 32, ragged contexts U[1024,131072], single pass"),
 }
@@ -283,14 +285,14 @@ def cpu_baseline(pz, wl, oracle, torch, layer, n_seq):
 
 class Model:
     """The heterogeneous 36-layer decode step: every layer appends one token per sequence and runs
-    its attention (window 128: single pass; window 8192 and full: split-K 1024 + merge)."""
+    its attention (window 128: single pass; window 8192 and full: split-K with `split_tokens`-long chunks + merge)."""
 
-    def __init__(self, pz, wl, torch, kv_dtype, keep_context_types=()):
+    def __init__(self, pz, wl, torch, kv_dtype, keep_context_types=(), split_tokens=1024):
         self.pattern = wl.layer_pattern(seed=5)
         self.layers = []
         kept = set()
         for i, w in enumerate(self.pattern):
-            spec = dict(B=32, L=(1024, 131072), window=w, split_tokens=0 if w == 128 else 1024,
+            spec = dict(B=32, L=(1024, 131072), window=w, split_tokens=0 if w == 128 else split_tokens,
                         outlier_frac=0.0, seed=5, bounded=True)
             keep = w in keep_context_types and w not in kept
             kept.add(w) if keep else None
@@ -341,9 +343,12 @@ def run_cfg5(args, pz, wl, torch):
     """36 layers: 18 x window 128, 8 x window 8192, 10 x full; batch 32, contexts U[1024,131072]."""
     text = ("cfg5: 36-layer decode step (18 x window-128, 8 x window-8192, 10 x full attention), batch 32, ragged "
             "contexts U[1024,131072], 64 q / 8 KV heads, d=64, paged E4M3 KV with per-layer K/V scales; every layer "
-            "= kv_append of 1 token/seq + decode attention (+ LSE merge)")
+            "= kv_append of 1 token/seq + decode attention (+ LSE merge; split-K chunks of %d tokens)" % (
+                args.split_tokens if args.split_tokens is not None else CFG5_SPLIT))
     t0 = time.perf_counter()
-    model = Model(pz, wl, torch, pz.KV_FP8, keep_context_types=(128, 8192, 0) if args.cpu_seqs > 0 else ())
+    split5 = args.split_tokens if args.split_tokens is not None else CFG5_SPLIT
+    model = Model(pz, wl, torch, pz.KV_FP8, keep_context_types=(128, 8192, 0) if args.cpu_seqs > 0 else (),
+                  split_tokens=split5)
     log("built the 36 FP8 layer caches in %.1f s" % (time.perf_counter() - t0))
     ms_step, _ = time_model(torch, model, args.steps, args.warmup, events=False)
     reps = [ms_step] + [time_model(torch, model, args.steps, 1, events=False)[0] for _ in range(3)]
@@ -408,7 +413,7 @@ def run_cfg5(args, pz, wl, torch):
     if not args.no_bf16:
         del model
         torch.cuda.empty_cache()
-        mb = Model(pz, wl, torch, pz.KV_BF16)
+        mb = Model(pz, wl, torch, pz.KV_BF16, split_tokens=split5)
         ms_b, _ = time_model(torch, mb, args.steps, args.warmup, events=False)
         sb = float(sum(l.step_bytes(wl) for l in mb.layers))
         result["bf16_kv"] = {"ms_per_step": ms_b, "GBps": sb / (ms_b * 1e-3) / 1e9,
