@@ -36,6 +36,24 @@ __device__ __forceinline__ unsigned pack_hi16(float first, float second) {
     return __builtin_amdgcn_perm(__float_as_uint(second), __float_as_uint(first), 0x07060302u);
 }
 
+// What truncation to bf16 dropped from p: p - bf16_trunc(p), exact, in one v_dot2c_f32_bf16 on the
+// packed pair that already holds the truncated values: (first, second) . (-1, -0) + p.  The
+// constants are spelled with a -0 half so that neither is an inline constant of the instruction
+// (the inline -1.0 of a packed-bf16 operand selects the other half).
+__device__ __forceinline__ float residual_first(unsigned packed, float p) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), __builtin_bit_cast(bf16x2, 0x8000bf80u), p,
+                                           false);
+}
+__device__ __forceinline__ float residual_second(unsigned packed, float p) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), __builtin_bit_cast(bf16x2, 0xbf808000u), p,
+                                           false);
+}
+
+// max(a, b) for a, b below FLT_MAX as the median of (a, b, FLT_MAX): one v_med3_f32.  fmaxf() costs up to three
+// instructions wherever the compiler cannot prove that an operand is not a signalling NaN
+// (lane-swap results, loop-carried values): it first quiets each such operand.
+__device__ __forceinline__ float max2(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, 3.4028234663852886e38f); }
+
 __device__ __forceinline__ float fmax3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
@@ -45,9 +63,9 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 // yields (low half twice | high half twice), so two swaps and two max operations reduce over the rows.
 __device__ __forceinline__ float rows_max(float x) {
     u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const float y = max2(__uint_as_float(a[0]), __uint_as_float(a[1]));
     u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
-    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    return max2(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
 __device__ __forceinline__ float bf16_round_to_f32bits(float x, uint16_t *bits) {

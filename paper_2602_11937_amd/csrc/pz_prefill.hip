@@ -140,16 +140,15 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
                         for (int r = 0; r < 4; ++r)
                             sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
                 }
-                float mx = fmax3(sacc[0][0], sacc[0][1], sacc[0][2]);
-                mx = fmax3(mx, sacc[0][3], sacc[1][0]);
-                mx = fmax3(mx, sacc[1][1], sacc[1][2]);
-                mx = fmax3(mx, sacc[1][3], sacc[2][0]);
-                mx = fmax3(mx, sacc[2][1], sacc[2][2]);
-                mx = fmax3(mx, sacc[2][3], sacc[3][0]);
-                mx = fmax3(mx, sacc[3][1], sacc[3][2]);
-                mx = fmaxf(mx, sacc[3][3]);
+                float mx = max2(sacc[0][0], sacc[0][1]);
+                mx = fmax3(mx, sacc[0][2], sacc[0][3]);
+#pragma unroll
+                for (int j = 1; j < 4; ++j) {
+                    mx = fmax3(mx, sacc[j][0], sacc[j][1]);
+                    mx = fmax3(mx, sacc[j][2], sacc[j][3]);
+                }
                 mx = rows_max(mx);
-                const float m_new = fmaxf(m[u], mx * sc);
+                const float m_new = max2(m[u], mx * sc);
                 // a column may have seen no attended position yet (its window starts later)
                 const float m_ref = (m_new == -INFINITY) ? 0.f : m_new;
                 const float alpha = __builtin_amdgcn_exp2f(m[u] - m_ref);
@@ -164,10 +163,9 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
                 for (int i = 0; i < 16; i += 2) {
                     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i / 4][i % 4], sc, -m_ref));
                     const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[(i + 1) / 4][(i + 1) % 4], sc, -m_ref));
-                    const float r0 = p0 - __uint_as_float(__float_as_uint(p0) & 0xffff0000u);
-                    const float r1 = p1 - __uint_as_float(__float_as_uint(p1) & 0xffff0000u);
-                    ph[i / 8][(i % 8) / 2] = pack_hi16(p0, p1);
-                    pl[i / 8][(i % 8) / 2] = pack_hi16(r0, r1);
+                    const unsigned hi = pack_hi16(p0, p1);
+                    ph[i / 8][(i % 8) / 2] = hi;
+                    pl[i / 8][(i % 8) / 2] = pack_hi16(residual_first(hi, p0), residual_second(hi, p1));
                 }
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
