@@ -355,6 +355,28 @@ def test_balanced_partition_degenerate_batches(monkeypatch):
             assert rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("lens,split,window", [
+    ("many_short", 64, 0),                   # 1024 sequences of 0..200 tokens: 16 strips of lengths in the partition
+    ([131072], 64, 0),                       # one sequence, 2048 chunks
+    ([100000, 5], 65536, 0),                 # chunks longer than most contexts
+    ([131072, 70000], 1024, 8192),           # window layer at the longest context
+    ([500, 64, 63, 1], 64, 1),               # a window of one token: the newest token alone
+    ([500, 64, 65, 1], 64, 63), ([500, 64, 65, 1], 64, 64), ([500, 64, 65, 1], 0, 65),
+])
+def test_extreme_shapes(lens, split, window):
+    if lens == "many_short":
+        rng = np.random.default_rng(1024)
+        lens = rng.integers(0, 201, size=1024).tolist()
+    case = wl.make_case("x", B=len(lens), Hq=8, Hkv=2, d=64, P=64, seq_lens=lens, window=window, seed=len(lens) + window)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    want = oracle_attn(case, kc, vc, accum="f64")
+    got = gpu_attn(case, cache, split_tokens=split)
+    assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL
+    if window == 1:                           # softmax over one logit and the sink
+        assert np.all(got[np.asarray(lens) == 0] == 0)
+
+
 @pytest.mark.parametrize("waves,cpg,balanced", [(1, 1, 0), (1, 2, 0), (1, 3, 0), (1, 8, 0), (1, 1, 1), (2, 1, 1),
                                                 (4, 1, 1), (8, 1, 1)])
 def test_every_launch_shape_gives_the_same_answer(waves, cpg, balanced, monkeypatch):
