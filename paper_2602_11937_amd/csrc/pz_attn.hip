@@ -375,25 +375,30 @@ __device__ __forceinline__ float wave_sum(float x) {
     return x;
 }
 
-// Merge kernel: one wave per (sequence, query head).  The chunks are taken 64 at a time: lane i
-// fetches (m_i, l_i) of chunk i and computes its weight exp(m_i - M); then lane = channel and the
-// 64 accumulator rows are streamed, all 64 loads of a lane in flight together, each row scaled by
-// its chunk's weight read out of the weight register (uniform lane index).  The first batch is
-// fetched before the sequence length is known; rows of chunks beyond the sequence (which the first
-// pass does not write) are inside the workspace, so the read is safe, and they are discarded.
-__global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParams prm) {
+// Merge kernel: one workgroup of W waves per (sequence, query head).  The chunks are taken 64 at a
+// time (wave w takes batches w, w + W, ...): lane i fetches (m_i, l_i) of chunk i and computes its
+// weight exp(m_i - M); then lane = channel and the 64 accumulator rows are streamed, all 64 loads
+// of a lane in flight together, each row scaled by its chunk's weight read out of the weight
+// register (uniform lane index).  A wave's first batch is fetched before the sequence length is
+// known; rows of chunks beyond the sequence (which the first pass does not write) are inside the
+// workspace, so the read is safe, and they are discarded.  With W > 1 (more than 64 chunks: each
+// batch is a dependent round trip to memory, so they are spread over waves) the waves' running
+// (M, numerator, denominator) meet in LDS and wave 0, which also carries the sink, finishes.
+template <int W>
+__global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int S = prm.n_splits;
     const float *acc = prm.ws_acc + (int64_t)row * S * 64;
     const float2 *ml = reinterpret_cast<const float2 *>(prm.ws_ml) + (int64_t)row * S;
-    const float sink = prm.sinks != nullptr ? prm.sinks[h] : -INFINITY;
+    const float sink = (prm.sinks != nullptr && wave == 0) ? prm.sinks[h] : -INFINITY;
     float M = sink;                                    // running reference maximum
     float num = 0.f;
     float den = (sink == -INFINITY) ? 0.f : 1.0f;      // exp(sink - M) with M == sink
     int n = S;
-    for (int base = 0; base < n; base += 64) {
+    bool first = true;
+    for (int base = 64 * wave; base < n; base += 64 * W) {
         const int cnt = min(64, S - base);             // rows that exist
         float2 v = {-INFINITY, 0.f};
         if (lane < cnt) v = ml[base + lane];
@@ -401,12 +406,13 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParam
         float x[64];
 #pragma unroll
         for (int u = 0; u < 64; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
-        if (base == 0 && prm.seq_lens != nullptr) {    // chunks past this bound were never written
+        if (first && prm.seq_lens != nullptr) {        // chunks past this bound were never written
             const int L = prm.seq_lens[b];
             const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
             const int span = L - (lo & ~63);
             n = min(S, (span + prm.split_tokens - 1) / prm.split_tokens);
         }
+        first = false;
         if (base + lane >= n) v = float2{-INFINITY, 0.f};
         const float M_new = fmaxf(M, wave_max(v.x));
         if (M_new == -INFINITY) continue;              // only empty partials so far, no sink
@@ -421,6 +427,31 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const pz::ReduceParam
             // rows past the sequence's chunks may hold anything (the first batch is fetched before
             // the bound is known), so they are dropped by a select, not by a zero weight
             num = __builtin_fmaf(base + u < n ? x[u] : 0.f, wu, num);
+        }
+    }
+    if constexpr (W > 1) {
+        __shared__ float part[W][66];                  // numerator[64], M, denominator of every wave
+        part[wave][lane] = num;
+        if (lane == 0) {
+            part[wave][64] = M;
+            part[wave][65] = den;
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        float M_all = M;
+#pragma unroll
+        for (int w = 1; w < W; ++w) M_all = fmaxf(M_all, part[w][64]);
+        if (M_all != -INFINITY) {
+            const float f0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((M - M_all) * kLog2e);
+            num *= f0;
+            den *= f0;
+#pragma unroll
+            for (int w = 1; w < W; ++w) {
+                const float Mw = part[w][64];
+                const float f = (Mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((Mw - M_all) * kLog2e);
+                num = __builtin_fmaf(part[w][lane], f, num);
+                den = __builtin_fmaf(part[w][65], f, den);
+            }
         }
     }
     const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
@@ -453,7 +484,12 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
 }
 
 hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(prm.B * prm.Hq)), dim3(64), 0, stream, prm);
+    // one wave per 64 chunks, at most eight
+    const dim3 grid((unsigned)(prm.B * prm.Hq));
+    if (prm.n_splits <= 64) hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, dim3(64), 0, stream, prm);
+    else if (prm.n_splits <= 128) hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, dim3(128), 0, stream, prm);
+    else if (prm.n_splits <= 256) hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, dim3(256), 0, stream, prm);
+    else hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, dim3(512), 0, stream, prm);
     return hipGetLastError();
 }
 

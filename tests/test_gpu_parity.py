@@ -270,15 +270,22 @@ def test_partials_match_the_chunked_oracle():
         assert rel_err(avg_g, avg_o) <= TOL
 
 
-def test_reduce_kernel_alone_against_oracle_reduce():
-    rng = np.random.default_rng(19)
-    B, Hq, S, d = 3, 16, 7, 64
+@pytest.mark.parametrize("S", [7, 64, 65, 128, 130, 256, 300, 513, 1100])
+def test_reduce_kernel_alone_against_oracle_reduce(S):
+    """The merge on synthetic partials; 64 chunks per wave, so the counts cover one to eight waves per row,
+    full and ragged last batches, and waves that see only empty partials."""
+    rng = np.random.default_rng(19 + S)
+    B, Hq, d = 4, 16, 64
     acc = rng.standard_normal((B, Hq, S, d)).astype(np.float32)
     ml = np.stack([rng.standard_normal((B, Hq, S)) * 20, rng.uniform(1, 900, (B, Hq, S))], -1).astype(np.float32)
     ml[0, :, 3] = (-np.inf, 0)
     acc[0, :, 3] = 0
     ml[1] = (-np.inf, 0)                                            # a row with only empty partials
     acc[1] = 0
+    ml[2, :, :max(1, S - 70)] = (-np.inf, 0)                        # only the last batches hold anything
+    acc[2, :, :max(1, S - 70)] = 0
+    ml[3, :, S // 2:] = (-np.inf, 0)                                # only the first ones do
+    acc[3, :, S // 2:] = 0
     sinks = rng.standard_normal(Hq).astype(np.float32)
     ws = torch.from_numpy(np.concatenate([acc.ravel(), ml.ravel()])).to(DEV)
     for sk in (sinks, None):
