@@ -120,15 +120,17 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
             }
             if (prefetch)
                 load_v<P, EB>(vt, vbase + (int64_t)page_id((s + 1) * NPS + geom.vslot - pbase) * page_bytes, geom.voff);
-#pragma unroll
-            for (int u = 0; u < NT; ++u) {
-                f32x4 sacc[4];
+            // the four pieces of one column tile's work on this step
+            auto qk = [&](int u, f32x4 (&sacc)[4]) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     f32x4 z = {0.f, 0.f, 0.f, 0.f};
                     z = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j][0], qb[u][0], z, 0, 0, 0);
                     sacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[j][1], qb[u][1], z, 0, 0, 0);
                 }
+            };
+            // mask, running maximum, rescale of what is accumulated; returns the reference maximum
+            auto head = [&](int u, f32x4 (&sacc)[4]) -> float {
                 // causal / window mask of this lane's column (a column without a query keeps its
                 // garbage: it is never written out)
                 const bool col_full = !live[u] || (base >= lo_col[u] && base + 63 <= p_col[u]);
@@ -158,7 +160,9 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
                     for (int c = 0; c < 4; ++c) o[u][c] *= alpha;
                     lsum[u] *= alpha;
                 }
-                u32x4 ph[2], pl[2];
+                return m_ref;
+            };
+            auto expo = [&](const f32x4 (&sacc)[4], float m_ref, u32x4 (&ph)[2], u32x4 (&pl)[2]) {
 #pragma unroll
                 for (int i = 0; i < 16; i += 2) {
                     const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i / 4][i % 4], sc, -m_ref));
@@ -167,6 +171,8 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
                     ph[i / 8][(i % 8) / 2] = hi;
                     pl[i / 8][(i % 8) / 2] = pack_hi16(residual_first(hi, p0), residual_second(hi, p1));
                 }
+            };
+            auto pv = [&](int u, const u32x4 (&ph)[2], const u32x4 (&pl)[2]) {
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
                     const bf16x8 bh = __builtin_bit_cast(bf16x8, ph[s2]), bl = __builtin_bit_cast(bf16x8, pl[s2]);
@@ -178,6 +184,15 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
                         o[u][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[c][s2], bl, o[u][c], 0, 0, 0);
                     }
                 }
+            };
+#pragma unroll
+            for (int u = 0; u < NT; ++u) {
+                f32x4 sacc[4];
+                u32x4 ph[2], pl[2];
+                qk(u, sacc);
+                const float m_ref = head(u, sacc);
+                expo(sacc, m_ref, ph, pl);
+                pv(u, ph, pl);
             }
         };
         load_k<P, EB>(kt, kbase + (int64_t)page_id(gs * NPS + geom.kslot - pbase) * page_bytes, geom.koff);
