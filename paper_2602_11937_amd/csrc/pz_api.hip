@@ -21,9 +21,16 @@ pz_status check_cache(const pz_cache *c) {
 bool positive_finite(float x) { return x > 0.0f && isfinite(x); }
 
 // Query heads per KV head the attention kernels take: a column tile holds 8 heads, so up to 8
-// directly; an even group of up to 16 runs as two virtual KV heads of half the group each, both
-// reading the same cache head.
-bool group_supported(int group) { return group >= 1 && (group <= 8 || (group <= 16 && group % 2 == 0)); }
+// directly; a larger group runs as 2, 4 or 8 virtual KV heads of an equal part of the group each,
+// all reading the same cache head.  Returns log2 of the number of virtual heads per KV head, or -1
+// when no such split gives parts of at most 8 heads (odd groups above 8, groups above 64, ...).
+int group_shift(int group) {
+    if (group < 1) return -1;
+    for (int k = 0; k <= 3; ++k)
+        if (group % (1 << k) == 0 && (group >> k) <= 8) return k;
+    return -1;
+}
+bool group_supported(int group) { return group_shift(group) >= 0; }
 
 int env_int(const char *name, int fallback) {
     const char *s = getenv(name);
@@ -155,7 +162,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
         return PZ_ERR_NULL;
     }
     const int n_chunks = split_tokens > 0 ? n_splits : 1;
-    if ((int64_t)batch * cache->n_kv_heads * 2 * n_chunks > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+    if ((int64_t)batch * cache->n_kv_heads * 8 * n_chunks > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
 
     pz::AttnParams p;
     p.k = static_cast<uint8_t *>(cache->k);
@@ -176,7 +183,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     p.B = batch;
     p.Hq = n_q_heads;
     p.cache_heads = cache->n_kv_heads;
-    p.head_shift = n_q_heads / cache->n_kv_heads > 8 ? 1 : 0;
+    p.head_shift = group_shift(n_q_heads / cache->n_kv_heads);
     p.Hkv = cache->n_kv_heads << p.head_shift;
     p.G = n_q_heads / p.Hkv;
     p.window = window;
@@ -280,7 +287,7 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     if (q == nullptr || q_start == nullptr || block_table == nullptr || seq_lens == nullptr || out == nullptr)
         return PZ_ERR_NULL;
     const int tiles = (max_new_tokens + 2 * PZ_PREFILL_NT - 1) / (2 * PZ_PREFILL_NT);
-    if ((int64_t)batch * tiles * cache->n_kv_heads * 2 > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
+    if ((int64_t)batch * tiles * cache->n_kv_heads * 8 > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;
     pz::PrefillParams p;
     p.k = static_cast<const uint8_t *>(cache->k);
     p.v = static_cast<const uint8_t *>(cache->v);
@@ -294,7 +301,7 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     p.B = batch;
     p.Hq = n_q_heads;
     p.cache_heads = cache->n_kv_heads;
-    p.head_shift = n_q_heads / cache->n_kv_heads > 8 ? 1 : 0;
+    p.head_shift = group_shift(n_q_heads / cache->n_kv_heads);
     p.Hkv = cache->n_kv_heads << p.head_shift;
     p.G = n_q_heads / p.Hkv;
     p.window = window;

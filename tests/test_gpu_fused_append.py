@@ -21,6 +21,7 @@ GEOMETRIES = {
     "window": dict(B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 128, 129, 50], window=128),
     "window_unaligned": dict(B=3, Hq=16, Hkv=2, d=64, P=16, seq_lens=[1000, 333, 20], window=300),
     "g16_two_virtual_heads": dict(B=3, Hq=32, Hkv=2, d=64, P=64, seq_lens=[700, 64, 1300]),
+    "g32_four_virtual_heads": dict(B=2, Hq=64, Hkv=2, d=64, P=64, seq_lens=[900, 65]),
 }
 
 
