@@ -39,7 +39,7 @@ MEASURED_TRAFFIC_BYTES = {"cfg3": 1092826799}
 METRIC = "decode-attention GB/s (% of HBM peak) + attn tokens/s, B=16 ctx=64K FP8 KV"
 HBM_PEAK_GBPS = 8000.0
 CFG5_SPLIT = 8192      # split-K chunk length of cfg5's full and window-8192 layers (the configuration names none;
-                       # 8192 measured best: 1024 4.16 ms, 2048 4.11, 4096 3.90, 8192 3.85, 16384 4.11)
+                       # 8192 measured best: 1024 4.17 ms, 2048 4.03, 4096 3.81, 8192 3.77, 16384 4.11)
 
 WORKLOADS = {
     # name: (B, seq_lens spec, window, split_tokens, outlier_frac, seed, instances, description)

@@ -409,14 +409,20 @@ static int balanced_slots(int page_size, int elem_bytes) {
 }
 
 hipError_t launch_decode_attn_balanced(const AttnParams &prm_in, int page_size, int elem_bytes, hipStream_t stream) {
-    // workgroups per KV head: as many as the kernel activates when every sequence has the longest length
-    // (it never activates more), and never more than fit the device at once
+    // workgroups per KV head: twice as many as the kernel activates when every sequence has the longest
+    // length (shorter sequences mean fewer chunks, for which the plan may want smaller shares and hence up
+    // to twice the workgroups), never more than there are chunks or than fit the device at once
     AttnParams prm = prm_in;
     const unsigned cap_chunks = (unsigned)prm.B * (unsigned)prm.n_splits;
     unsigned bph = (unsigned)(balanced_slots(page_size, elem_bytes) / prm.Hkv);
     if (bph < 1) bph = 1;
     balanced_plan(cap_chunks, (unsigned)prm.Hkv, bph, &prm.full_n_act, &prm.full_q, &prm.full_r);
-    bph = prm.full_n_act;
+    {
+        unsigned room = prm.full_n_act * 2u;
+        if (room > cap_chunks) room = cap_chunks;
+        if (room > bph) room = bph;
+        bph = room < prm.full_n_act ? prm.full_n_act : room;
+    }
     const dim3 grid((unsigned)(bph * prm.Hkv)), block(64);
     const size_t lds_bytes = kPark * 528 * sizeof(float);
 #define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, lds_bytes, stream, prm)

@@ -36,12 +36,14 @@ struct AttnParams {
 hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream);
 
 // Balanced partition of `tot` chunks of one KV head over at most `bph` workgroups: n_act shares, the
-// first r of q + 1 chunks, the others of q.  About 4 chunks per share while that still gives 2048
-// waves over all heads, fewer for small jobs, more when the grid is capped; with k = q + 1 (or q when
-// r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ are the smaller ones.
+// first r of q + 1 chunks, the others of q.  The share size aimed at is the one that leaves about
+// 1024 waves over all heads -- one per SIMD; measured best on this chip for shares of 64 to 256
+// steps -- but at most 4 chunks (the partials a wave can park), and 1 for small jobs; it grows past
+// that only when the grid is capped.  With k = q + 1 (or q when r == 0) the largest share,
+// n_act = ceil(tot / k), so the shares that differ are the smaller ones.
 __host__ __device__ inline void balanced_plan(unsigned tot, unsigned n_heads, unsigned bph, unsigned *n_act,
                                               unsigned *q, unsigned *r) {
-    unsigned want = tot * n_heads / 2048u;
+    unsigned want = (tot * n_heads + 512u) / 1024u;
     want = want < 1u ? 1u : (want > 4u ? 4u : want);
     unsigned cap = (tot + want - 1u) / want;
     if (cap > bph) cap = bph;
