@@ -384,7 +384,8 @@ __device__ __forceinline__ float wave_sum(float x) {
 // workspace, so the read is safe, and they are discarded.  With W > 1 (more than 64 chunks: each
 // batch is a dependent round trip to memory, so they are spread over waves) the waves' running
 // (M, numerator, denominator) meet in LDS and wave 0, which also carries the sink, finishes.
-template <int W>
+// NB = chunks per batch (64, or 16 for rows of at most 16 chunks so that a short row does not issue 64 loads).
+template <int W, int NB>
 __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
@@ -398,14 +399,14 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
     float den = (sink == -INFINITY) ? 0.f : 1.0f;      // exp(sink - M) with M == sink
     int n = S;
     bool first = true;
-    for (int base = 64 * wave; base < n; base += 64 * W) {
-        const int cnt = min(64, S - base);             // rows that exist
+    for (int base = NB * wave; base < n; base += NB * W) {
+        const int cnt = min(NB, S - base);             // rows that exist
         float2 v = {-INFINITY, 0.f};
         if (lane < cnt) v = ml[base + lane];
         const float *a = acc + (int64_t)base * 64 + lane;
-        float x[64];
+        float x[NB];
 #pragma unroll
-        for (int u = 0; u < 64; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
+        for (int u = 0; u < NB; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
         if (first && prm.seq_lens != nullptr) {        // chunks past this bound were never written
             const int L = prm.seq_lens[b];
             const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
@@ -422,7 +423,7 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
         den = den * keep + wave_sum(v.y * w);
         M = M_new;
 #pragma unroll
-        for (int u = 0; u < 64; ++u) {
+        for (int u = 0; u < NB; ++u) {
             const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
             // rows past the sequence's chunks may hold anything (the first batch is fetched before
             // the bound is known), so they are dropped by a select, not by a zero weight
@@ -484,12 +485,13 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
 }
 
 hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
-    // one wave per 64 chunks, at most eight
+    // one wave per 64 chunks, at most eight; short rows in one batch of 16
     const dim3 grid((unsigned)(prm.B * prm.Hq));
-    if (prm.n_splits <= 64) hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, dim3(64), 0, stream, prm);
-    else if (prm.n_splits <= 128) hipLaunchKernelGGL(splitk_reduce_kernel<2>, grid, dim3(128), 0, stream, prm);
-    else if (prm.n_splits <= 256) hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, dim3(256), 0, stream, prm);
-    else hipLaunchKernelGGL(splitk_reduce_kernel<8>, grid, dim3(512), 0, stream, prm);
+    if (prm.n_splits <= 16) hipLaunchKernelGGL((splitk_reduce_kernel<1, 16>), grid, dim3(64), 0, stream, prm);
+    else if (prm.n_splits <= 64) hipLaunchKernelGGL((splitk_reduce_kernel<1, 64>), grid, dim3(64), 0, stream, prm);
+    else if (prm.n_splits <= 128) hipLaunchKernelGGL((splitk_reduce_kernel<2, 64>), grid, dim3(128), 0, stream, prm);
+    else if (prm.n_splits <= 256) hipLaunchKernelGGL((splitk_reduce_kernel<4, 64>), grid, dim3(256), 0, stream, prm);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<8, 64>), grid, dim3(512), 0, stream, prm);
     return hipGetLastError();
 }
 
