@@ -24,12 +24,14 @@
  *     divides into parts of at most 8 heads (10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64; the
  *     attention kernels then read each KV head once per part of its group).
  *
- *   - Launch shapes are chosen by the library.  Three environment variables override the choice,
+ *   - Launch shapes are chosen by the library.  Four environment variables override the choice,
  *     for tests and measurements only (results are the same for every shape):
  *       PZ_ATTN_WAVES=1|2|4|8            waves per workgroup of the decode-attention kernel
  *       PZ_ATTN_CHUNKS_PER_GROUP=n       consecutive split-K chunks walked by a one-wave workgroup
  *       PZ_ATTN_BALANCED=0               full-attention split-K on the fixed (sequence, chunk group)
  *                                        grid instead of the partition balanced over the batch
+ *       PZ_APPEND_FORM=tile|token        quantise-and-append as 64-token tiles (large appends) or as one
+ *                                        wave per (token, KV head) (decode-sized appends)
  *
  * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
  * discuss paging):

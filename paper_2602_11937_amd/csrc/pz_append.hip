@@ -11,6 +11,7 @@
 //     contiguous across the lanes of a wave when the tokens' slots are contiguous.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "pz_internal.h"
 #include "pz_quant.h"
@@ -85,11 +86,45 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
     }
 }
 
+// Decode-sized appends (a token or a few hundred): one wave per (token, KV head), lane = channel, so
+// that the launch spreads over the chip instead of 64-token tiles over a few workgroups.  K: the
+// wave writes the token's 64 contiguous elements; V: 64 stores a page row apart.
+template <int EB>
+__global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendParams prm) {
+    const int64_t t = blockIdx.x;
+    const int g = blockIdx.y, c = threadIdx.x;
+    const int P = prm.P, Hkv = prm.Hkv;
+    const unsigned kb16 = prm.k_new[(t * Hkv + g) * 64 + c], vb16 = prm.v_new[(t * Hkv + g) * 64 + c];
+    const int64_t slot = prm.slot_mapping[t];
+    if (slot < 0) return;
+    const int64_t page = slot / P, off = slot % P;
+    uint8_t *kd = prm.k + (((page * Hkv + g) * P + off) * 64 + c) * EB;
+    uint8_t *vd = prm.v + (((page * Hkv + g) * 64 + c) * P + off) * EB;
+    if constexpr (EB == 1) {
+        *kd = (uint8_t)quant_one(kb16, prm.k_scale);
+        *vd = (uint8_t)quant_one(vb16, prm.v_scale);
+    } else {
+        *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
+        *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
+    }
+}
+
 }  // namespace
 
 namespace pz {
 
 hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t stream) {
+    // up to two waves per SIMD: the token-per-wave form (PZ_APPEND_FORM=tile|token forces one, for tests)
+    const char *form = getenv("PZ_APPEND_FORM");
+    const bool token_form = form != nullptr && form[0] == 't' && form[1] == 'o'   ? true
+                            : form != nullptr && form[0] == 't' && form[1] == 'i' ? false
+                                                                                  : prm.T * prm.Hkv <= 8192;
+    if (token_form && prm.T <= 0x7fffffff) {
+        const dim3 grid((unsigned)prm.T, (unsigned)prm.Hkv), block(64);
+        if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_token_kernel<1>, grid, block, 0, stream, prm);
+        else hipLaunchKernelGGL(kv_append_token_kernel<2>, grid, block, 0, stream, prm);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)((prm.T + 63) / 64), (unsigned)prm.Hkv), block(256);
     if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_kernel<1>, grid, block, 0, stream, prm);
     else hipLaunchKernelGGL(kv_append_kernel<2>, grid, block, 0, stream, prm);

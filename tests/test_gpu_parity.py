@@ -27,9 +27,16 @@ def oracle_attn(case, kc, vc, **kw):
 
 # ------------------------------------------------------------------ append: bit-exact
 
+@pytest.fixture(params=["tile", "token"])
+def append_form(request, monkeypatch):
+    """Both launch forms of the append kernel (64-token tiles / one wave per token and head)."""
+    monkeypatch.setenv("PZ_APPEND_FORM", request.param)
+    return request.param
+
+
 @pytest.mark.parametrize("P", [16, 32, 64])
 @pytest.mark.parametrize("scales", ["amax", "pow2", "unit"])
-def test_append_bytes_bit_exact(P, scales):
+def test_append_bytes_bit_exact(P, scales, append_form):
     case = wl.make_case("a", B=3, Hq=8, Hkv=2, d=64, P=P, seq_lens=[100, 37, 129], seed=P,
                         pow2_scales=scales == "pow2", unit_scales=scales == "unit", outlier_frac=0.05)
     cache = gpu_cache(case)
@@ -38,7 +45,7 @@ def test_append_bytes_bit_exact(P, scales):
     assert np.array_equal(gk, ok) and np.array_equal(gv, ov)      # includes untouched canary bytes
 
 
-def test_append_every_bf16_value_and_negative_slots():
+def test_append_every_bf16_value_and_negative_slots(append_form):
     Hkv, d, P = 2, 64, 16
     T = 65536 // (Hkv * d)
     bits = np.arange(65536, dtype=np.uint16).reshape(T, Hkv, d)
@@ -61,7 +68,7 @@ def test_append_every_bf16_value_and_negative_slots():
         assert np.array_equal(gv[~nan_v], ov[~nan_v]) and np.all((gv[nan_v] & 0x7F) == 0x7F)
 
 
-def test_append_divides_on_inputs_where_the_reciprocal_product_gives_another_code():
+def test_append_divides_on_inputs_where_the_reciprocal_product_gives_another_code(append_form):
     """Inputs whose quotient sits on a midpoint between two codes, so that x * (1 / scale) and x / scale
     quantise differently: the kernel must produce the division's code, as the oracle does."""
     from helpers import division_sensitive_inputs
@@ -87,7 +94,7 @@ def test_append_divides_on_inputs_where_the_reciprocal_product_gives_another_cod
     assert n_checked >= 40
 
 
-def test_append_bf16_cache_copies_bits():
+def test_append_bf16_cache_copies_bits(append_form):
     case = wl.make_case("b", B=2, Hq=8, Hkv=2, d=64, P=32, seq_lens=[70, 33], seed=1)
     cache = gpu_cache(case, dtype=pz.KV_BF16)
     gk, gv = to_oracle_layout(cache)
@@ -95,7 +102,7 @@ def test_append_bf16_cache_copies_bits():
     assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
 
 
-def test_append_single_decode_token_per_sequence():
+def test_append_single_decode_token_per_sequence(append_form):
     """The decode-step shape: one new token per sequence lands in an already filled cache."""
     case = wl.make_case("c", B=5, Hq=8, Hkv=2, d=64, P=64, seq_lens=[65, 64, 1, 200, 128], seed=2)
     last = case.offsets[1:] - 1
