@@ -24,7 +24,7 @@
  *     divides into parts of at most 8 heads (10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64; the
  *     attention kernels then read each KV head once per part of its group).
  *
- *   - Launch shapes are chosen by the library.  Four environment variables override the choice,
+ *   - Launch shapes are chosen by the library.  Five environment variables override the choice,
  *     for tests and measurements only (results are the same for every shape):
  *       PZ_ATTN_WAVES=1|2|4|8            waves per workgroup of the decode-attention kernel
  *       PZ_ATTN_CHUNKS_PER_GROUP=n       consecutive split-K chunks walked by a one-wave workgroup
@@ -32,6 +32,8 @@
  *                                        grid instead of the partition balanced over the batch
  *       PZ_APPEND_FORM=tile|token        quantise-and-append as 64-token tiles (large appends) or as one
  *                                        wave per (token, KV head) (decode-sized appends)
+ *       PZ_APPEND_FUSED=1|0              pz_decode_attn_append writes the new token inside the attention
+ *                                        launch (small batches) or by a launch of its own first
  *
  * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
  * discuss paging):
@@ -159,11 +161,13 @@ pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
                          size_t workspace_bytes, void *out, int32_t out_dtype, void *hip_stream);
 
 /*
- * pz_kv_append_fp8 of one new token per sequence fused into pz_decode_attn (one launch less per
- * decode step: at decode sizes the append is launch-bound).  The paper's decode step quantises the
- * new token's K/V into the FP8 cache and then attends over the cache including that token (Section 3,
- * "KV Quantization"); this call does both, with the same arithmetic and the same bytes as the two
- * separate calls.
+ * pz_kv_append_fp8 of one new token per sequence and pz_decode_attn in one call.  The paper's decode
+ * step quantises the new token's K/V into the FP8 cache and then attends over the cache including
+ * that token (Section 3, "KV Quantization"); this call does both, with the same arithmetic and the
+ * same bytes as the two separate calls.  For small batches the append runs inside the attention
+ * launch (one launch less per decode step: at decode sizes the append is launch-bound); from 512
+ * (sequence, KV head) pairs on, where that is slower, the call enqueues an append kernel of its own
+ * first -- it needs no slot mapping either way.
  *
  *   k_new, v_new : bf16 [batch][n_kv_heads][head_dim]; row b is written to the slot of position
  *                  L_b - 1 of sequence b, i.e. block_table[b][(L_b-1)/page_size] * page_size +

@@ -167,8 +167,15 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     pz::AttnParams p;
     p.k = static_cast<uint8_t *>(cache->k);
     p.v = static_cast<uint8_t *>(cache->v);
-    p.k_new = fused_append ? static_cast<const uint16_t *>(k_new) : nullptr;
-    p.v_new = fused_append ? static_cast<const uint16_t *>(v_new) : nullptr;
+    // The append runs inside the attention launch for small batches.  From 512 (sequence, KV head) pairs on
+    // the scattered V bytes of that many tokens hold the attention kernel up by more than a launch costs
+    // (batch 256: + 28 us), so the token is appended by a launch of its own first: same bytes, same results.
+    // PZ_APPEND_FUSED=1|0 forces either way (tests).
+    bool in_kernel = fused_append && (int64_t)batch * cache->n_kv_heads < 512;
+    if (fused_append && getenv("PZ_APPEND_FUSED") != nullptr) in_kernel = !env_is_zero("PZ_APPEND_FUSED");
+    if (cache->n_kv_heads > 65535) in_kernel = fused_append;      // the append launch has one grid row per KV head
+    p.k_new = in_kernel ? static_cast<const uint16_t *>(k_new) : nullptr;
+    p.v_new = in_kernel ? static_cast<const uint16_t *>(v_new) : nullptr;
     p.k_scale = k_scale;
     p.q = static_cast<const uint16_t *>(q);
     p.block_table = block_table;
@@ -203,6 +210,22 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     p.chunks_per_group = chunks_per_group;
     const int elem_bytes = cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2;
     hipError_t e;
+    if (fused_append && !in_kernel) {
+        pz::AppendParams a;
+        a.k = p.k;
+        a.v = p.v;
+        a.k_new = static_cast<const uint16_t *>(k_new);
+        a.v_new = static_cast<const uint16_t *>(v_new);
+        a.slot_mapping = nullptr;
+        a.T = batch;
+        a.Hkv = cache->n_kv_heads;
+        a.P = cache->page_size;
+        a.k_scale = k_scale;
+        a.v_scale = v_scale;
+        e = pz::launch_kv_append_last(a, block_table, max_pages_per_seq, seq_lens, batch, elem_bytes,
+                                      static_cast<hipStream_t>(hip_stream));
+        if (e != hipSuccess) return PZ_ERR_LAUNCH;
+    }
     // Full-attention split-K with one-wave workgroups: the chunks are dealt out evenly on the device from
     // the actual lengths (PZ_ATTN_BALANCED=0 keeps the one-workgroup-per-chunk-group grid, for
     // comparisons).  Window layers keep that grid: their sequences all span about the window, and

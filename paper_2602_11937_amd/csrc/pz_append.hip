@@ -109,9 +109,41 @@ __global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendPar
     }
 }
 
+// The newest token of every sequence, placed from the block table and the lengths (no slot mapping):
+// position L_b - 1 of sequence b.  One wave per (sequence, KV head), lane = channel.
+template <int EB>
+__global__ __launch_bounds__(64) void kv_append_last_kernel(const pz::AppendParams prm, const int32_t *__restrict__ block_table,
+                                                            int max_pages, const int32_t *__restrict__ seq_lens) {
+    const int b = blockIdx.x, g = blockIdx.y, c = threadIdx.x;
+    const int P = prm.P, Hkv = prm.Hkv;
+    const int L = seq_lens[b];
+    const unsigned kb16 = prm.k_new[((int64_t)b * Hkv + g) * 64 + c], vb16 = prm.v_new[((int64_t)b * Hkv + g) * 64 + c];
+    if (L <= 0) return;
+    const int pos = L - 1;
+    const int64_t page = block_table[(int64_t)b * max_pages + pos / P];
+    const int off = pos % P;
+    uint8_t *kd = prm.k + (((page * Hkv + g) * P + off) * 64 + c) * EB;
+    uint8_t *vd = prm.v + (((page * Hkv + g) * 64 + c) * P + off) * EB;
+    if constexpr (EB == 1) {
+        *kd = (uint8_t)quant_one(kb16, prm.k_scale);
+        *vd = (uint8_t)quant_one(vb16, prm.v_scale);
+    } else {
+        *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
+        *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
+    }
+}
+
 }  // namespace
 
 namespace pz {
+
+hipError_t launch_kv_append_last(const AppendParams &prm, const int32_t *block_table, int max_pages,
+                                 const int32_t *seq_lens, int batch, int elem_bytes, hipStream_t stream) {
+    const dim3 grid((unsigned)batch, (unsigned)prm.Hkv), block(64);
+    if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_last_kernel<1>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
+    else hipLaunchKernelGGL(kv_append_last_kernel<2>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
+    return hipGetLastError();
+}
 
 hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t stream) {
     // up to two waves per SIMD: the token-per-wave form (PZ_APPEND_FORM=tile|token forces one, for tests)

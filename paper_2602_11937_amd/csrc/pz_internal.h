@@ -110,6 +110,8 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
                               hipStream_t stream);
 hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream);
 hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t stream);
+hipError_t launch_kv_append_last(const AppendParams &prm, const int32_t *block_table, int max_pages,
+                                 const int32_t *seq_lens, int batch, int elem_bytes, hipStream_t stream);
 hipError_t launch_kv_amax(const uint16_t *k, const uint16_t *v, int64_t n, float *amax, hipStream_t stream);
 hipError_t launch_kv_scales(const float *amax, int round_up_pow2, float *scales, hipStream_t stream);
 

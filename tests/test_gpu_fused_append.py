@@ -21,6 +21,7 @@ GEOMETRIES = {
     "window": dict(B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 128, 129, 50], window=128),
     "window_unaligned": dict(B=3, Hq=16, Hkv=2, d=64, P=16, seq_lens=[1000, 333, 20], window=300),
     "g16_two_virtual_heads": dict(B=3, Hq=32, Hkv=2, d=64, P=64, seq_lens=[700, 64, 1300]),
+    "batch_70_hkv8": dict(B=70, Hq=8, Hkv=8, d=64, P=16, seq_lens=[1 + (37 * i) % 150 for i in range(70)]),
     "g32_four_virtual_heads": dict(B=2, Hq=64, Hkv=2, d=64, P=64, seq_lens=[900, 65]),
 }
 
@@ -58,9 +59,17 @@ def run_pair(case, split_tokens, dtype=pz.KV_FP8):
     return res
 
 
+@pytest.fixture(params=["in_kernel", "own_launch"])
+def fused_way(request, monkeypatch):
+    """pz_decode_attn_append writes the token inside the attention launch (small batches) or by a launch of
+    its own first (from 512 (sequence, KV head) pairs on); force each."""
+    monkeypatch.setenv("PZ_APPEND_FUSED", "1" if request.param == "in_kernel" else "0")
+    return request.param
+
+
 @pytest.mark.parametrize("name", list(GEOMETRIES))
 @pytest.mark.parametrize("split_tokens", [0, 64, 256])
-def test_fused_equals_append_then_attention(name, split_tokens):
+def test_fused_equals_append_then_attention(name, split_tokens, fused_way):
     case = wl.make_case(name, seed=70 + len(name), **GEOMETRIES[name])
     (out_a, cache_a), (out_b, cache_b) = run_pair(case, split_tokens)
     assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v)     # canary bytes included
@@ -73,7 +82,7 @@ def test_fused_equals_append_then_attention(name, split_tokens):
     assert rel_err(out_b.cpu().numpy(), want) <= TOL
 
 
-def test_fused_append_into_a_bf16_cache():
+def test_fused_append_into_a_bf16_cache(fused_way):
     case = wl.make_case("b", B=3, Hq=16, Hkv=2, d=64, P=32, seq_lens=[200, 32, 33], seed=81)
     for split in (0, 128):
         (out_a, cache_a), (out_b, cache_b) = run_pair(case, split, dtype=pz.KV_BF16)
@@ -90,7 +99,7 @@ def test_fused_append_under_every_launch_shape(waves, cpg, monkeypatch):
         assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v) and torch.equal(out_a, out_b)
 
 
-def test_a_decode_loop_of_fused_steps_matches_the_oracle():
+def test_a_decode_loop_of_fused_steps_matches_the_oracle(fused_way):
     """Twenty consecutive decode steps through the fused call, the sequences growing across page and
     chunk boundaries; after the last step the cache and the output equal the oracle's."""
     full = wl.make_case("l", B=3, Hq=16, Hkv=2, d=64, P=16, seq_lens=[90, 37, 150], seed=83)
