@@ -4,11 +4,15 @@
 // Section 3, "KV Quantization": FP8 KV cache with max-calibrated per-layer K and V scales); the
 // arithmetic of one value is in pz_quant.h.
 //
-// Work split: one workgroup = up to 64 tokens of one KV head.
-//   K ([page][head][P][64]): 4 threads per token, 16 channels each -> one 16-byte store; the 16
-//     tokens of a wave write 16 x 64 B rows (contiguous when their slots are).
-//   V ([page][head][64][P]): lane = token, each wave walks 16 channels -> byte stores that are
-//     contiguous across the lanes of a wave when the tokens' slots are contiguous.
+// Three launch forms, the same bytes:
+//   tile form (large appends: cache builds, prompts): one workgroup = up to 64 tokens of one KV head.
+//     K ([page][head][P][64]): 4 threads per token, 16 channels each -> one 16-byte store; the 16
+//       tokens of a wave write 16 x 64 B rows (contiguous when their slots are).
+//     V ([page][head][64][P]): lane = token, each wave walks 16 channels -> byte stores that are
+//       contiguous across the lanes of a wave when the tokens' slots are contiguous.
+//   token form (decode-sized appends): one wave per (token, KV head), lane = channel.
+//   last-token form (inside pz_decode_attn_append for large batches): as the token form, placed
+//     from the block table and the sequence lengths instead of a slot mapping.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -86,18 +90,12 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
     }
 }
 
-// Decode-sized appends (a token or a few hundred): one wave per (token, KV head), lane = channel, so
-// that the launch spreads over the chip instead of 64-token tiles over a few workgroups.  K: the
-// wave writes the token's 64 contiguous elements; V: 64 stores a page row apart.
+// One token's row of one KV head, lane = channel c.  K: the wave writes the token's 64 contiguous
+// elements; V: 64 stores a page row apart.
 template <int EB>
-__global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendParams prm) {
-    const int64_t t = blockIdx.x;
-    const int g = blockIdx.y, c = threadIdx.x;
+__device__ __forceinline__ void put_token(const pz::AppendParams &prm, int64_t page, int off, int g, int c,
+                                          unsigned kb16, unsigned vb16) {
     const int P = prm.P, Hkv = prm.Hkv;
-    const unsigned kb16 = prm.k_new[(t * Hkv + g) * 64 + c], vb16 = prm.v_new[(t * Hkv + g) * 64 + c];
-    const int64_t slot = prm.slot_mapping[t];
-    if (slot < 0) return;
-    const int64_t page = slot / P, off = slot % P;
     uint8_t *kd = prm.k + (((page * Hkv + g) * P + off) * 64 + c) * EB;
     uint8_t *vd = prm.v + (((page * Hkv + g) * 64 + c) * P + off) * EB;
     if constexpr (EB == 1) {
@@ -109,28 +107,32 @@ __global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendPar
     }
 }
 
-// The newest token of every sequence, placed from the block table and the lengths (no slot mapping):
-// position L_b - 1 of sequence b.  One wave per (sequence, KV head), lane = channel.
+// Decode-sized appends (a token or a few hundred): one wave per (token, KV head), so that the launch
+// spreads over the chip instead of 64-token tiles over a few workgroups.
 template <int EB>
-__global__ __launch_bounds__(64) void kv_append_last_kernel(const pz::AppendParams prm, const int32_t *__restrict__ block_table,
-                                                            int max_pages, const int32_t *__restrict__ seq_lens) {
+__global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendParams prm) {
+    const int64_t t = blockIdx.x;
+    const int g = blockIdx.y, c = threadIdx.x;
+    const int64_t src = (t * prm.Hkv + g) * 64 + c;
+    const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
+    const int64_t slot = prm.slot_mapping[t];
+    if (slot < 0) return;
+    put_token<EB>(prm, slot / prm.P, (int)(slot % prm.P), g, c, kb16, vb16);
+}
+
+// The newest token of every sequence, placed from the block table and the lengths (no slot mapping):
+// position L_b - 1 of sequence b.  One wave per (sequence, KV head).
+template <int EB>
+__global__ __launch_bounds__(64) void kv_append_last_kernel(const pz::AppendParams prm,
+                                                            const int32_t *__restrict__ block_table, int max_pages,
+                                                            const int32_t *__restrict__ seq_lens) {
     const int b = blockIdx.x, g = blockIdx.y, c = threadIdx.x;
-    const int P = prm.P, Hkv = prm.Hkv;
     const int L = seq_lens[b];
-    const unsigned kb16 = prm.k_new[((int64_t)b * Hkv + g) * 64 + c], vb16 = prm.v_new[((int64_t)b * Hkv + g) * 64 + c];
+    const int64_t src = ((int64_t)b * prm.Hkv + g) * 64 + c;
+    const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
     if (L <= 0) return;
     const int pos = L - 1;
-    const int64_t page = block_table[(int64_t)b * max_pages + pos / P];
-    const int off = pos % P;
-    uint8_t *kd = prm.k + (((page * Hkv + g) * P + off) * 64 + c) * EB;
-    uint8_t *vd = prm.v + (((page * Hkv + g) * 64 + c) * P + off) * EB;
-    if constexpr (EB == 1) {
-        *kd = (uint8_t)quant_one(kb16, prm.k_scale);
-        *vd = (uint8_t)quant_one(vb16, prm.v_scale);
-    } else {
-        *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
-        *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
-    }
+    put_token<EB>(prm, block_table[(int64_t)b * max_pages + pos / prm.P], pos % prm.P, g, c, kb16, vb16);
 }
 
 }  // namespace
