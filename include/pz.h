@@ -164,10 +164,10 @@ pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
  * pz_kv_append_fp8 of one new token per sequence and pz_decode_attn in one call.  The paper's decode
  * step quantises the new token's K/V into the FP8 cache and then attends over the cache including
  * that token (Section 3, "KV Quantization"); this call does both, with the same arithmetic and the
- * same bytes as the two separate calls.  For small batches the append runs inside the attention
- * launch (one launch less per decode step: at decode sizes the append is launch-bound); from 512
- * (sequence, KV head) pairs on, where that is slower, the call enqueues an append kernel of its own
- * first -- it needs no slot mapping either way.
+ * same bytes as the two separate calls.  For small batches and for single-pass calls the append runs
+ * inside the attention launch (one launch less per decode step: at decode sizes the append is
+ * launch-bound); in split-K calls over 512 or more (sequence, KV head) pairs, where that is slower,
+ * the call enqueues an append kernel of its own first -- it needs no slot mapping either way.
  *
  *   k_new, v_new : bf16 [batch][n_kv_heads][head_dim]; row b is written to the slot of position
  *                  L_b - 1 of sequence b, i.e. block_table[b][(L_b-1)/page_size] * page_size +

@@ -21,6 +21,8 @@ GEOMETRIES = {
     "window": dict(B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 128, 129, 50], window=128),
     "window_unaligned": dict(B=3, Hq=16, Hkv=2, d=64, P=16, seq_lens=[1000, 333, 20], window=300),
     "g16_two_virtual_heads": dict(B=3, Hq=32, Hkv=2, d=64, P=64, seq_lens=[700, 64, 1300]),
+    "window128_single_pass": dict(B=6, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 128, 129, 1, 65, 193], window=128),
+    "window20_p16_single_pass": dict(B=4, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37, 16, 17], window=20),
     "batch_70_hkv8": dict(B=70, Hq=8, Hkv=8, d=64, P=16, seq_lens=[1 + (37 * i) % 150 for i in range(70)]),
     "g32_four_virtual_heads": dict(B=2, Hq=64, Hkv=2, d=64, P=64, seq_lens=[900, 65]),
 }

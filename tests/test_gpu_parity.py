@@ -394,6 +394,34 @@ def test_extreme_shapes(lens, split, window):
         assert np.all(got[np.asarray(lens) == 0] == 0)
 
 
+@pytest.mark.parametrize("P", [16, 32, 64])
+@pytest.mark.parametrize("window", [1, 20, 64, 128, 129])
+@pytest.mark.parametrize("kv_dtype", [pz.KV_FP8, pz.KV_BF16])
+def test_short_windows_single_pass(P, window, kv_dtype):
+    """Single-pass calls over one to three steps: every alignment of a short window against the 64-position
+    steps, contexts shorter than the window, empty sequences, both cache types and both output types."""
+    lens = [0, 1, 63, 64, 65, 127, 128, 129, 191, 192, 193, 255, 256, 257, 1000, 1001, 4033]
+    case = wl.make_case("sw", B=len(lens), Hq=16, Hkv=2, d=64, P=P, seq_lens=lens, window=window, seed=window + P)
+    ks, vs = (case.k_scale, case.v_scale) if kv_dtype == pz.KV_FP8 else (1.0, 1.0)
+    cache = gpu_cache(case, dtype=kv_dtype, k_scale=ks, v_scale=vs)
+    kc, vc = oracle_cache(case, oracle.KV_FP8 if kv_dtype == pz.KV_FP8 else oracle.KV_BF16)
+    want = oracle_attn(case, kc, vc, k_scale=ks, v_scale=vs, accum="f64")
+    got = gpu_attn(case, cache, k_scale=ks, v_scale=vs)
+    assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL and np.all(got[0] == 0)
+    b16 = gpu_attn(case, cache, k_scale=ks, v_scale=vs, out_dtype=pz.OUT_BF16)
+    assert np.array_equal(b16, torch.from_numpy(got).to(torch.bfloat16).float().numpy())
+
+
+def test_short_contexts_without_a_window():
+    """Full attention, single pass, over contexts of at most 192 positions (a block table of three steps)."""
+    case = wl.make_case("sc", B=5, Hq=24, Hkv=2, d=64, P=16, seq_lens=[192, 1, 100, 0, 129], seed=31)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    assert case.max_pages * case.P <= 192
+    got = gpu_attn(case, cache)
+    assert rel_err(got, oracle_attn(case, kc, vc, accum="f64")) <= TOL
+
+
 @pytest.mark.parametrize("waves,cpg,balanced", [(1, 1, 0), (1, 2, 0), (1, 3, 0), (1, 8, 0), (1, 1, 1), (2, 1, 1),
                                                 (4, 1, 1), (8, 1, 1)])
 def test_every_launch_shape_gives_the_same_answer(waves, cpg, balanced, monkeypatch):
