@@ -20,9 +20,8 @@
  *     PZ_ERR_LAUNCH.  Out-of-range block-table entries or slots are the caller's bug and are
  *     not detected.
  *   - Supported shapes: head_dim == 64; page_size in {16, 32, 64}; n_q_heads a multiple of
- *     n_kv_heads with group size n_q_heads / n_kv_heads <= 8, or a group size that 2, 4 or 8
- *     divides into parts of at most 8 heads (10, 12, 14, 16, 20, 24, 28, 32, 40, 48, 56, 64; the
- *     attention kernels then read each KV head once per part of its group).
+ *     n_kv_heads with group size n_q_heads / n_kv_heads <= 64 (a group above 8 is cut into 2, 4
+ *     or 8 parts of at most 8 heads and the attention kernels read each KV head once per part).
  *
  *   - Launch shapes are chosen by the library.  Five environment variables override the choice,
  *     for tests and measurements only (results are the same for every shape):

@@ -21,13 +21,13 @@ pz_status check_cache(const pz_cache *c) {
 bool positive_finite(float x) { return x > 0.0f && isfinite(x); }
 
 // Query heads per KV head the attention kernels take: a column tile holds 8 heads, so up to 8
-// directly; a larger group runs as 2, 4 or 8 virtual KV heads of an equal part of the group each,
-// all reading the same cache head.  Returns log2 of the number of virtual heads per KV head, or -1
-// when no such split gives parts of at most 8 heads (odd groups above 8, groups above 64, ...).
+// directly; a larger group runs as 2, 4 or 8 virtual KV heads that all read the same cache head,
+// each with a part of ceil(group / parts) heads (the last part holds what is left, possibly
+// nothing).  Returns log2 of the number of virtual heads per KV head, or -1 for groups above 64.
 int group_shift(int group) {
     if (group < 1) return -1;
     for (int k = 0; k <= 3; ++k)
-        if (group % (1 << k) == 0 && (group >> k) <= 8) return k;
+        if (((group + (1 << k) - 1) >> k) <= 8) return k;
     return -1;
 }
 bool group_supported(int group) { return group_shift(group) >= 0; }
@@ -194,7 +194,8 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     p.cache_heads = cache->n_kv_heads;
     p.head_shift = group_shift(n_q_heads / cache->n_kv_heads);
     p.Hkv = cache->n_kv_heads << p.head_shift;
-    p.G = n_q_heads / p.Hkv;
+    p.G_full = n_q_heads / cache->n_kv_heads;
+    p.G = (p.G_full + (1 << p.head_shift) - 1) >> p.head_shift;
     p.window = window;
     p.split_tokens = split_tokens;
     p.n_splits = split_tokens > 0 ? n_splits : 1;
@@ -328,7 +329,8 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     p.cache_heads = cache->n_kv_heads;
     p.head_shift = group_shift(n_q_heads / cache->n_kv_heads);
     p.Hkv = cache->n_kv_heads << p.head_shift;
-    p.G = n_q_heads / p.Hkv;
+    p.G_full = n_q_heads / cache->n_kv_heads;
+    p.G = (p.G_full + (1 << p.head_shift) - 1) >> p.head_shift;
     p.window = window;
     p.out_dtype = out_dtype;
     p.tiles_per_seq = tiles;

@@ -65,10 +65,15 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     const int bg = blockIdx.x % (prm.B * prm.Hkv);
     const int cgrp = (int)(gridDim.x / (prm.B * prm.Hkv)) - 1 - (int)(blockIdx.x / (prm.B * prm.Hkv));
     const int b = bg / prm.Hkv, g = bg % prm.Hkv;
-    const int G = prm.G;
+    // heads of this virtual KV head: a group above 8 is cut into parts of prm.G heads, the last part may be
+    // smaller (or empty: then there is nothing to do)
+    const int part = g & ((1 << prm.head_shift) - 1);
+    const int G = min(prm.G, prm.G_full - part * prm.G);
+    const int q_first = (g >> prm.head_shift) * prm.G_full + part * prm.G;   // first query head of the part
+    if (G <= 0) return;
     const int n = lane & 15, kb = lane >> 4;
     const int head = n & 7;
-    const int qh = g * G + head;                       // only meaningful when head < G
+    const int qh = q_first + head;                       // only meaningful when head < G
 
     // One-wave workgroups of full-attention layers know their first step without the sequence
     // length, so their first block-table read is issued beside the read of the length instead
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                 const int r = r0 + 4 * u + (lane >> 4);
                 if (r < n_rows) {
                     const int cl = r / G, h = r - cl * G;
-                    const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c_first + cl;
+                    const int64_t row = ((int64_t)b * prm.Hq + q_first + h) * prm.n_splits + c_first + cl;
                     __builtin_nontemporal_store(x[u], reinterpret_cast<f32x4 *>(prm.ws_acc + row * 64 + 4 * quad));
                 }
             }
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         // (m, l) pairs: one lane per (chunk, head)
         for (int r = lane; r < n_rows; r += 64) {
             const int cl = r / G, h = r - cl * G;
-            const int64_t row = ((int64_t)b * prm.Hq + g * G + h) * prm.n_splits + c_first + cl;
+            const int64_t row = ((int64_t)b * prm.Hq + q_first + h) * prm.n_splits + c_first + cl;
             float2 ml;
             ml.x = lds[cl * 528 + 512 + h];
             ml.y = lds[cl * 528 + 520 + h];
@@ -333,7 +338,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
 
     for (int idx = threadIdx.x; idx < G * 64; idx += blockDim.x) {
         const int h = idx >> 6, c = idx & 63;
-        const int qhead = g * G + h;
+        const int qhead = q_first + h;
         float M = -INFINITY;
         for (int w = 0; w < n_waves; ++w) M = fmaxf(M, sm_m[w][h]);
         float sink2 = -INFINITY;

@@ -55,7 +55,6 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     const int lane = threadIdx.x;
     const int n = lane & 15, kb = lane >> 4;
     const int head = n & 7;
-    const int G = prm.G;
     // Workgroup t works on share t / Hkv of KV head (t + t / Hkv) % Hkv.  The active shares are the lowest
     // ones, so the workgroups that stream are the first of the grid and are placed like a launch of
     // just that many (the idle rest is dispatched after them and leaves at once); the rotation makes
@@ -63,6 +62,12 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     const int bph = gridDim.x / prm.Hkv;               // workgroups per KV head
     const int i_blk = blockIdx.x / prm.Hkv;
     const int g = (blockIdx.x + i_blk) % prm.Hkv;
+    // heads of this virtual KV head: a group above 8 is cut into parts of prm.G heads, the last part may be
+    // smaller (or empty: then there is nothing to do)
+    const int part = g & ((1 << prm.head_shift) - 1);
+    const int G = min(prm.G, prm.G_full - part * prm.G);
+    const int q_first = (g >> prm.head_shift) * prm.G_full + part * prm.G;   // first query head of the part
+    if (G <= 0) return;
     const int split = prm.split_tokens;
     const int steps_per_chunk = split >> 6;
 
@@ -174,7 +179,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     const uint8_t *kbase = prm.k + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
     const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
     const float sc = prm.sc;
-    const int qh = g * G + head;                       // only meaningful when head < G
+    const int qh = q_first + head;                       // only meaningful when head < G
 
     WaveState st;
     auto reset_state = [&]() {
@@ -220,14 +225,14 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 const int r = r0 + 4 * u + (lane >> 4);
                 if (r < n_rows) {
                     const int cl = r / G, h = r - cl * G;
-                    const int64_t row = ((int64_t)bb * prm.Hq + g * G + h) * prm.n_splits + chunk0 + cl;
+                    const int64_t row = ((int64_t)bb * prm.Hq + q_first + h) * prm.n_splits + chunk0 + cl;
                     __builtin_nontemporal_store(x[u], reinterpret_cast<f32x4 *>(prm.ws_acc + row * 64 + 4 * quad));
                 }
             }
         }
         for (int r = lane; r < n_rows; r += 64) {      // (m, l) pairs: one lane per (chunk, head)
             const int cl = r / G, h = r - cl * G;
-            const int64_t row = ((int64_t)bb * prm.Hq + g * G + h) * prm.n_splits + chunk0 + cl;
+            const int64_t row = ((int64_t)bb * prm.Hq + q_first + h) * prm.n_splits + chunk0 + cl;
             __builtin_nontemporal_store(lds[cl * 528 + 512 + h], prm.ws_ml + row * 2);
             __builtin_nontemporal_store(lds[cl * 528 + 520 + h], prm.ws_ml + row * 2 + 1);
         }

@@ -24,6 +24,7 @@ struct AttnParams {
     float k_scale;               // for the fused append only (the logits use sc)
     int32_t max_pages, B, Hq, Hkv, G;   // Hkv, G: "virtual" KV heads of at most 8 query heads each
     int32_t cache_heads, head_shift;    // KV heads of the cache; virtual head g reads cache head g >> head_shift
+    int32_t G_full;                     // query heads per cache KV head (G = heads per virtual head, the part size)
     int32_t window, split_tokens, n_splits, out_dtype;
     int32_t chunks_per_group;    // consecutive split-K chunks walked by one workgroup (1 unless it is one wave)
     // balanced kernel: the partition of a batch whose sequences all have n_splits chunks, worked out on
@@ -88,7 +89,7 @@ struct PrefillParams {
     const float *sinks;
     void *out;                   // [T][Hq][64]
     int32_t max_pages, B, Hq, Hkv, G, window, out_dtype, tiles_per_seq;   // Hkv, G: virtual heads as in AttnParams
-    int32_t cache_heads, head_shift;
+    int32_t cache_heads, head_shift, G_full;
     float sc, v_scale;
 };
 

@@ -33,7 +33,12 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
     const int g = blockIdx.x % prm.Hkv;                // KV head fastest: tiles of a head share an XCD's L2
     const int tile = (blockIdx.x / prm.Hkv) % prm.tiles_per_seq;
     const int b = blockIdx.x / (prm.Hkv * prm.tiles_per_seq);
-    const int G = prm.G;
+    // heads of this virtual KV head: a group above 8 is cut into parts of prm.G heads, the last part may be
+    // smaller (or empty: then there is nothing to do)
+    const int part = g & ((1 << prm.head_shift) - 1);
+    const int G = min(prm.G, prm.G_full - part * prm.G);
+    const int q_first = (g >> prm.head_shift) * prm.G_full + part * prm.G;   // first query head of the part
+    if (G <= 0) return;
 
     const int q0 = prm.q_start[b], n_new = prm.q_start[b + 1] - q0;
     const int i0 = tile * QT;
@@ -53,7 +58,7 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
         lo_col[u] = (W > 0 && p_col[u] + 1 > W) ? p_col[u] + 1 - W : 0;
         u32x4 a = {0, 0, 0, 0}, c = {0, 0, 0, 0};
         if (live[u]) {
-            const uint16_t *qrow = prm.q + ((int64_t)(q0 + i) * prm.Hq + g * G + head) * 64 + 16 * kb;
+            const uint16_t *qrow = prm.q + ((int64_t)(q0 + i) * prm.Hq + q_first + head) * 64 + 16 * kb;
             a = *reinterpret_cast<const u32x4 *>(qrow);
             c = *reinterpret_cast<const u32x4 *>(qrow + 8);
         }
@@ -206,7 +211,7 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
     for (int u = 0; u < NT; ++u) {
         if (!live[u]) continue;
         const int i = i0 + 2 * u + tok_in_tile;
-        const int qh = g * G + head;
+        const int qh = q_first + head;
         const float sink2 = prm.sinks != nullptr ? prm.sinks[qh] * kLog2e : -INFINITY;
         const float M = fmaxf(m[u], sink2);
         const float f = (m[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m[u] - M);

@@ -63,11 +63,10 @@ def test_decode_attn_rejects_bad_arguments_before_any_launch():
     assert attn(cache(head_dim=128)) == UNSUP and attn(cache(page_size=48)) == UNSUP
     assert attn(cache(dtype=7)) == UNSUP
     assert attn(cache(), n_q_heads=60) == SHAPE                      # not a multiple of the KV heads
-    assert attn(cache(n_kv_heads=2), n_q_heads=18) == UNSUP          # odd group above 8
-    assert attn(cache(n_kv_heads=2), n_q_heads=36) == UNSUP          # 18: halves of 9, no quarters
-    assert attn(cache(n_kv_heads=1), n_q_heads=72) == UNSUP          # above 64
+    assert attn(cache(n_kv_heads=1), n_q_heads=65) == UNSUP          # groups above 64
+    assert attn(cache(n_kv_heads=1), n_q_heads=72) == UNSUP
     assert attn(cache(n_kv_heads=1), n_q_heads=128) == UNSUP
-    for hq in (32, 64, 48, 40, 128):                                 # groups of 16, 32, 24, 20, 64 are taken
+    for hq in (18, 22, 32, 34, 64, 48, 40, 128):                     # groups of 9, 11, 16, 17, 32, 24, 20, 64 are taken
         assert attn(cache(n_kv_heads=2), n_q_heads=hq, batch=0) == 0
     assert attn(cache(), batch=-1) == SHAPE and attn(cache(), window=-5) == SHAPE
     assert attn(cache(), sm_scale=0.0) == SHAPE and attn(cache(), k_scale=-1.0) == SHAPE
@@ -158,7 +157,7 @@ def test_new_entry_points_reject_bad_arguments():
                                   a["sm"], a["ks"], a["vs"], a["w"], a["out"], a["odt"], stream=0, check=False)
     assert pre(None) == -1 and pre(c, qs=None) == -1 and pre(c, out=None) == -1
     assert pre(c, hq=60) == -2 and pre(c, mx=-1) == -2 and pre(c, sm=0.0) == -2
-    assert pre(c, hq=72) == -3 and pre(c, odt=5) == -3             # a group of 9 heads
+    assert pre(cache(n_kv_heads=1), hq=65) == -3 and pre(c, odt=5) == -3    # a group of 65 heads
     assert pre(c, b=0) == 0 and pre(c, mx=0) == 0
     # page pool
     assert lib.pz_page_pool_create(4, 16, 1, 0, 0) is None

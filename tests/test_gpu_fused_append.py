@@ -25,6 +25,8 @@ GEOMETRIES = {
     "window20_p16_single_pass": dict(B=4, Hq=8, Hkv=2, d=64, P=16, seq_lens=[100, 37, 16, 17], window=20),
     "batch_70_hkv8": dict(B=70, Hq=8, Hkv=8, d=64, P=16, seq_lens=[1 + (37 * i) % 150 for i in range(70)]),
     "g32_four_virtual_heads": dict(B=2, Hq=64, Hkv=2, d=64, P=64, seq_lens=[900, 65]),
+    "g9_uneven_parts": dict(B=3, Hq=18, Hkv=2, d=64, P=64, seq_lens=[700, 64, 130]),
+    "g33_empty_part": dict(B=2, Hq=33, Hkv=1, d=64, P=16, seq_lens=[200, 17]),
 }
 
 

@@ -134,13 +134,18 @@ CASES = {
     "pow2_scales": dict(B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[500, 70], pow2_scales=True, seed=10),
     "unit_scales": dict(B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[500, 70], unit_scales=True, seed=11),
     "len_one_and_zero": dict(B=4, Hq=8, Hkv=2, d=64, P=16, seq_lens=[1, 2, 17, 1], seed=12),
-    # groups above 8 run as 2, 4 or 8 virtual KV heads of an equal part of the group each
+    # groups above 8 run as 2, 4 or 8 virtual KV heads of a part of the group each
     "g16": dict(B=3, Hq=32, Hkv=2, d=64, P=64, seq_lens=[700, 64, 1300], seed=13),
     "g12_window": dict(B=2, Hq=36, Hkv=3, d=64, P=16, seq_lens=[300, 90], window=100, seed=14),
     "g10_hkv1": dict(B=2, Hq=10, Hkv=1, d=64, P=32, seq_lens=[257, 31], seed=15),
     "g32_four_virtual_heads": dict(B=2, Hq=64, Hkv=2, d=64, P=64, seq_lens=[900, 70], seed=16),
     "g24_window": dict(B=2, Hq=24, Hkv=1, d=64, P=16, seq_lens=[400, 130], window=150, seed=17),
     "g64_multi_query": dict(B=2, Hq=64, Hkv=1, d=64, P=64, seq_lens=[1500, 64], seed=18),
+    # odd groups: the last part of a group is smaller (9 = 5 + 4, 11 = 6 + 5, 17 = 5 + 5 + 5 + 2) or empty (33 = 6 x 5 + 3 + 0)
+    "g9": dict(B=3, Hq=18, Hkv=2, d=64, P=64, seq_lens=[700, 64, 1300], seed=19),
+    "g11_window": dict(B=2, Hq=11, Hkv=1, d=64, P=16, seq_lens=[300, 90], window=100, seed=20),
+    "g17": dict(B=2, Hq=34, Hkv=2, d=64, P=32, seq_lens=[257, 31], seed=21),
+    "g33_empty_part": dict(B=2, Hq=33, Hkv=1, d=64, P=64, seq_lens=[900, 70], seed=22),
 }
 
 

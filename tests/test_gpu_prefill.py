@@ -34,6 +34,8 @@ def gpu_prefill(case, cache, q, n_new, window, out_dtype=pz.OUT_F32):
     (dict(B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[500, 64, 1], sinks=False), [64, 0, 1]),   # a sequence without queries
     (dict(B=2, Hq=24, Hkv=2, d=64, P=64, seq_lens=[200, 77]), [9, 77]),         # G 12: two virtual heads per KV head
     (dict(B=2, Hq=32, Hkv=1, d=64, P=64, seq_lens=[150, 77]), [40, 77]),        # G 32: four
+    (dict(B=2, Hq=18, Hkv=2, d=64, P=64, seq_lens=[150, 77]), [40, 77]),        # G 9: parts of 5 and 4
+    (dict(B=1, Hq=33, Hkv=1, d=64, P=32, seq_lens=[130]), [130]),                # G 33: seven parts and an empty one
 ])
 @pytest.mark.parametrize("window", [0, 128, 50])
 def test_prefill_matches_oracle(kw, n_new, window):
