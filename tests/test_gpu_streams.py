@@ -57,3 +57,37 @@ def test_two_streams_step_two_layers_concurrently():
         torch.cuda.synchronize()
         for l, want in zip(layers, alone):
             assert torch.equal(l.out, want), rep
+
+
+def test_host_threads_call_the_library_concurrently():
+    """Four host threads, each stepping its own layer on its own stream (ctypes releases the GIL during a call):
+    the library's only shared state is an occupancy figure initialised once."""
+    import threading
+    layers = [LayerStep(60 + i, 0 if i % 2 == 0 else 200, 128 if i < 3 else 0) for i in range(4)]
+    alone = []
+    for l in layers:
+        l.step()
+        torch.cuda.synchronize()
+        alone.append(l.out.clone())
+        l.out.fill_(float("nan"))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in layers]
+    errors = []
+
+    def work(l, s):
+        try:
+            for _ in range(25):
+                l.step(stream=s)
+            s.synchronize()
+        except Exception as e:                                       # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(l, s)) for l, s in zip(layers, streams)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for l, want in zip(layers, alone):
+        assert torch.equal(l.out, want)
