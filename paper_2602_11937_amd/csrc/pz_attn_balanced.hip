@@ -26,9 +26,10 @@
 
 namespace {
 
-// Partials parked in LDS before a write-out (4 records of 2112 bytes leave room for four workgroups
-// per SIMD).  A share with more chunks is streamed in groups of at most this many.
-constexpr int kPark = 4;
+// Partials parked in LDS before a write-out: as many records of 2112 bytes as the largest share has
+// chunks, at most this many (16 records leave room for one workgroup per SIMD, which is what such
+// shares are planned for).  A share with more chunks is streamed in groups of that many.
+constexpr int kParkMax = 16;
 
 // Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS traffic): four shifted adds
 // inside every row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then
@@ -50,7 +51,7 @@ template <int P, int EB>
 __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
     constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
-    extern __shared__ float lds[];                     // kPark records of 528 floats (8 x 64 acc, 8 m, 8 l)
+    extern __shared__ float lds[];                     // prm.park records of 528 floats (8 x 64 acc, 8 m, 8 l)
 
     const int lane = threadIdx.x;
     const int n = lane & 15, kb = lane >> 4;
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         for (int gs = s0; gs < s1;) {
             // a group also ends where the LDS records run out, so that partials are written out only
             // between groups, where the pipeline is drained anyway
-            const int ge_park = a0_step + ((gs - a0_step) / steps_per_chunk + (kPark - parked)) * steps_per_chunk;
+            const int ge_park = a0_step + ((gs - a0_step) / steps_per_chunk + (prm.park - parked)) * steps_per_chunk;
             const int ge = min(min(gs + GROUP, s1), ge_park);
             const int pbase = gs * NPS;
             int ids0, ids1;
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
             }
             for (int s = gs; s + 1 < ge; ++s) step(s, true);
             step(ge - 1, false);
-            if (parked == kPark || ge == s1) {
+            if (parked == prm.park || ge == s1) {
                 if (parked > 0) write_out(b, park_chunk0, parked);
                 park_chunk0 += parked;
                 parked = 0;
@@ -386,13 +387,13 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
 
 namespace pz {
 
-// Workgroups of decode_attn_balanced_kernel<P, EB> that fit the device at once (one wave each): the
-// partition wants the whole grid resident, so the grid is never larger than this.  Worked out once per
-// kernel variant (function-local static: initialised once, also with several host threads).
+// Workgroups of decode_attn_balanced_kernel<P, EB> (one wave each, one LDS record) that fit the device at
+// once: the partition never plans more shares per launch than this.  Worked out once per kernel variant
+// (function-local static: initialised once, also with several host threads).
 template <int P, int EB>
 static int query_slots() {
     int per_cu = 0, dev = 0, cus = 0;
-    const size_t lds_bytes = kPark * 528 * sizeof(float);
+    const size_t lds_bytes = 528 * sizeof(float);
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_balanced_kernel<P, EB>, 64, lds_bytes) !=
             hipSuccess || per_cu <= 0)
         per_cu = 8;
@@ -429,7 +430,13 @@ hipError_t launch_decode_attn_balanced(const AttnParams &prm_in, int page_size, 
         bph = room < prm.full_n_act ? prm.full_n_act : room;
     }
     const dim3 grid((unsigned)(bph * prm.Hkv)), block(64);
-    const size_t lds_bytes = kPark * 528 * sizeof(float);
+    // no batch of shorter sequences is planned with larger shares than these (and one that were would
+    // only be written out in two goes)
+    unsigned k_full = prm.full_q + (prm.full_r > 0 ? 1u : 0u);
+    const unsigned want_full = balanced_want(cap_chunks, (unsigned)prm.Hkv);
+    if (k_full < want_full) k_full = want_full;
+    prm.park = (int)(k_full < 1u ? 1u : (k_full > (unsigned)kParkMax ? (unsigned)kParkMax : k_full));
+    const size_t lds_bytes = (size_t)prm.park * 528 * sizeof(float);
 #define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, lds_bytes, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);

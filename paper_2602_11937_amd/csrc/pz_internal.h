@@ -30,6 +30,7 @@ struct AttnParams {
     // balanced kernel: the partition of a batch whose sequences all have n_splits chunks, worked out on
     // the host (n_act shares; the first r hold q + 1 chunks, the others q)
     uint32_t full_n_act, full_q, full_r;
+    int32_t park;                // balanced kernel: LDS records (partials a wave parks before a write-out)
     float sc;                    // sm_scale * k_scale * log2(e)
     float v_scale;
 };
@@ -37,15 +38,18 @@ struct AttnParams {
 hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream);
 
 // Balanced partition of `tot` chunks of one KV head over at most `bph` workgroups: n_act shares, the
-// first r of q + 1 chunks, the others of q.  The share size aimed at is the one that leaves about
-// 1024 waves over all heads -- one per SIMD; measured best on this chip for shares of 64 to 256
-// steps -- but at most 4 chunks (the partials a wave can park), and 1 for small jobs; it grows past
-// that only when the grid is capped.  With k = q + 1 (or q when r == 0) the largest share,
-// n_act = ceil(tot / k), so the shares that differ are the smaller ones.
+// first r of q + 1 chunks, the others of q.  The share size aimed at is the smallest that leaves at
+// most 1024 waves over all heads -- one per SIMD, four per CU; measured best on this chip, ahead of
+// twice or four times as many shorter shares and far ahead of counts that fill the CUs unevenly --
+// but at most 16 chunks; it grows past that only when the grid is capped.  With k = q + 1 (or q when
+// r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ are the smaller ones.
+__host__ __device__ inline unsigned balanced_want(unsigned tot, unsigned n_heads) {
+    const unsigned want = (tot * n_heads + 1023u) / 1024u;
+    return want < 1u ? 1u : (want > 16u ? 16u : want);
+}
 __host__ __device__ inline void balanced_plan(unsigned tot, unsigned n_heads, unsigned bph, unsigned *n_act,
                                               unsigned *q, unsigned *r) {
-    unsigned want = (tot * n_heads + 512u) / 1024u;
-    want = want < 1u ? 1u : (want > 4u ? 4u : want);
+    const unsigned want = balanced_want(tot, n_heads);
     unsigned cap = (tot + want - 1u) / want;
     if (cap > bph) cap = bph;
     const unsigned k = (tot + cap - 1u) / cap;

@@ -65,8 +65,8 @@ def run_pair(case, split_tokens, dtype=pz.KV_FP8):
 
 @pytest.fixture(params=["in_kernel", "own_launch"])
 def fused_way(request, monkeypatch):
-    """pz_decode_attn_append writes the token inside the attention launch (small batches) or by a launch of
-    its own first (from 512 (sequence, KV head) pairs on); force each."""
+    """pz_decode_attn_append writes the token inside the attention launch (single-pass calls) or by a launch of
+    its own first (split-K calls); force each way for every call."""
     monkeypatch.setenv("PZ_APPEND_FUSED", "1" if request.param == "in_kernel" else "0")
     return request.param
 
