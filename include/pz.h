@@ -17,8 +17,16 @@
  *     returns.  Buffers must stay alive until the stream has run past the call.
  *   - Argument errors are detected on the host before anything is enqueued and are reported
  *     through the return value (never abort, never throw).  A failed launch gives
- *     PZ_ERR_LAUNCH.  Out-of-range block-table entries or slots are the caller's bug and are
- *     not detected.
+ *     PZ_ERR_LAUNCH.  What lives in device memory cannot be checked there: block-table entries,
+ *     sequence lengths and slots outside their ranges are the caller's bug and are not reported.
+ *     The kernels hold them to the buffers all the same -- a page id is cut to [0, num_pages), a
+ *     length to max_pages_per_seq * page_size (a negative one counts as 0), and a token whose slot
+ *     or page lies outside the cache is not written -- so such a sequence gets a meaningless row,
+ *     every other sequence its proper one, and no access leaves the cache or the block table.
+ *     (Not covered: q_start of the prefill call and positions of the rotary call, which index
+ *     buffers whose sizes the calls do not take.)
+ *   - Positions are 32-bit: max_pages_per_seq * page_size may not exceed 2^30 and
+ *     n_splits * split_tokens must stay below 2^31 (PZ_ERR_UNSUPPORTED otherwise).
  *   - Supported shapes: head_dim == 64; page_size in {16, 32, 64}; n_q_heads a multiple of
  *     n_kv_heads with group size n_q_heads / n_kv_heads <= 64 (a group above 8 is cut into 2, 4
  *     or 8 parts of at most 8 heads and the attention kernels read each KV head once per part).

@@ -18,6 +18,9 @@ pz_status check_cache(const pz_cache *c) {
     return PZ_OK;
 }
 
+// positions per sequence the kernels' 32-bit position arithmetic is sized for
+constexpr int64_t kMaxPositions = 1 << 30;
+
 bool positive_finite(float x) { return x > 0.0f && isfinite(x); }
 
 // Query heads per KV head the attention kernels take: a column tile holds 8 heads, so up to 8
@@ -110,6 +113,7 @@ pz_status pz_kv_append_fp8(const pz_cache *cache, const void *k_new, const void 
     p.T = n_tokens;
     p.Hkv = cache->n_kv_heads;
     p.P = cache->page_size;
+    p.num_slots = cache->num_pages * (int64_t)cache->page_size;
     p.k_scale = k_scale;
     p.v_scale = v_scale;
     const hipError_t e = pz::launch_kv_append(p, cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2,
@@ -146,6 +150,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
         return PZ_ERR_SHAPE;
     if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
     if (!group_supported(n_q_heads / cache->n_kv_heads)) return PZ_ERR_UNSUPPORTED;
+    if ((int64_t)max_pages_per_seq * cache->page_size > kMaxPositions) return PZ_ERR_UNSUPPORTED;
     if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
     if (!positive_finite(sm_scale) || !positive_finite(k_scale) || !positive_finite(v_scale))
         return PZ_ERR_SHAPE;
@@ -155,6 +160,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     if (fused_append && (k_new == nullptr || v_new == nullptr)) return PZ_ERR_NULL;
     if (split_tokens > 0) {
         if (n_splits <= 0) return PZ_ERR_SHAPE;
+        if ((int64_t)n_splits * split_tokens > 0x7fffffffLL) return PZ_ERR_UNSUPPORTED;   // positions are 32-bit
         if (workspace == nullptr) return PZ_ERR_WORKSPACE;
         if (workspace_bytes < pz_decode_attn_workspace_bytes(batch, n_q_heads, cache->head_dim, n_splits))
             return PZ_ERR_WORKSPACE;
@@ -189,6 +195,8 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
                   : nullptr;
     p.out = out;
     p.max_pages = max_pages_per_seq;
+    p.num_pages = (int32_t)cache->num_pages;
+    p.max_len = max_pages_per_seq * cache->page_size;
     p.B = batch;
     p.Hq = n_q_heads;
     p.cache_heads = cache->n_kv_heads;
@@ -223,6 +231,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
         a.T = batch;
         a.Hkv = cache->n_kv_heads;
         a.P = cache->page_size;
+        a.num_slots = cache->num_pages * (int64_t)cache->page_size;
         a.k_scale = k_scale;
         a.v_scale = v_scale;
         e = pz::launch_kv_append_last(a, block_table, max_pages_per_seq, seq_lens, batch, elem_bytes,
@@ -273,6 +282,7 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
     if (head_dim != 64) return PZ_ERR_UNSUPPORTED;
     if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
     if (seq_lens != nullptr && (split_tokens <= 0 || split_tokens % 64 != 0)) return PZ_ERR_SHAPE;
+    if (seq_lens != nullptr && split_tokens > kMaxPositions) return PZ_ERR_UNSUPPORTED;
     if (!positive_finite(v_scale)) return PZ_ERR_SHAPE;
     if (batch == 0) return PZ_OK;
     if (workspace == nullptr) return PZ_ERR_WORKSPACE;
@@ -307,6 +317,7 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || max_new_tokens < 0) return PZ_ERR_SHAPE;
     if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
     if (!group_supported(n_q_heads / cache->n_kv_heads)) return PZ_ERR_UNSUPPORTED;
+    if ((int64_t)max_pages_per_seq * cache->page_size > kMaxPositions) return PZ_ERR_UNSUPPORTED;
     if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
     if (!positive_finite(sm_scale) || !positive_finite(k_scale) || !positive_finite(v_scale)) return PZ_ERR_SHAPE;
     if (batch == 0 || max_new_tokens == 0) return PZ_OK;
@@ -324,6 +335,8 @@ pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q
     p.sinks = sinks;
     p.out = out;
     p.max_pages = max_pages_per_seq;
+    p.num_pages = (int32_t)cache->num_pages;
+    p.max_len = max_pages_per_seq * cache->page_size;
     p.B = batch;
     p.Hq = n_q_heads;
     p.cache_heads = cache->n_kv_heads;
@@ -393,6 +406,7 @@ pz_status pz_rope_kv_append_fp8(const pz_cache *cache, const void *q_in, void *q
     p.ap.T = n_tokens;
     p.ap.Hkv = cache->n_kv_heads;
     p.ap.P = cache->page_size;
+    p.ap.num_slots = cache->num_pages * (int64_t)cache->page_size;
     p.ap.k_scale = k_scale;
     p.ap.v_scale = v_scale;
     p.q_in = static_cast<const uint16_t *>(q_in);

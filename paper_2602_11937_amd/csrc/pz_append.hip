@@ -11,8 +11,9 @@
 //     V ([page][head][64][P]): lane = token, each wave walks 16 channels -> byte stores that are
 //       contiguous across the lanes of a wave when the tokens' slots are contiguous.
 //   token form (decode-sized appends): one wave per (token, KV head), lane = channel.
-//   last-token form (inside pz_decode_attn_append for large batches): as the token form, placed
-//     from the block table and the sequence lengths instead of a slot mapping.
+//   last-token form (split-K calls of pz_decode_attn_append): as the token form, placed from the block
+//     table and the sequence lengths instead of a slot mapping.
+// Tokens whose slot (or page) lies outside the cache are skipped in every form.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
             const u32x4 *src = reinterpret_cast<const u32x4 *>(prm.k_new + (t * Hkv + g) * 64 + part * 16);
             const u32x4 x0 = src[0], x1 = src[1];
             const int64_t slot = prm.slot_mapping[t];
-            if (slot >= 0) {
+            if (slot >= 0 && slot < prm.num_slots) {
                 const int64_t page = slot / P, off = slot % P;
                 uint8_t *dst = prm.k + (((page * Hkv + g) * P + off) * 64 + part * 16) * EB;
                 if constexpr (EB == 1) {
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
             const u32x4 x0 = reinterpret_cast<const u32x4 *>(src)[0];
             const u32x4 x1 = reinterpret_cast<const u32x4 *>(src)[1];
             const int64_t slot = prm.slot_mapping[t];
-            if (slot >= 0) {
+            if (slot >= 0 && slot < prm.num_slots) {
                 const int64_t page = slot / P, off = slot % P;
                 uint8_t *dst = prm.v + (((page * Hkv + g) * 64 + c0) * P + off) * EB;
 #pragma unroll
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendPar
     const int64_t src = (t * prm.Hkv + g) * 64 + c;
     const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
     const int64_t slot = prm.slot_mapping[t];
-    if (slot < 0) return;
+    if (slot < 0 || slot >= prm.num_slots) return;
     put_token<EB>(prm, slot / prm.P, (int)(slot % prm.P), g, c, kb16, vb16);
 }
 
@@ -130,9 +131,11 @@ __global__ __launch_bounds__(64) void kv_append_last_kernel(const pz::AppendPara
     const int L = seq_lens[b];
     const int64_t src = ((int64_t)b * prm.Hkv + g) * 64 + c;
     const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
-    if (L <= 0) return;
+    if (L <= 0 || L > max_pages * prm.P) return;           // no token, or a length the table row does not cover
     const int pos = L - 1;
-    put_token<EB>(prm, block_table[(int64_t)b * max_pages + pos / prm.P], pos % prm.P, g, c, kb16, vb16);
+    const int page = block_table[(int64_t)b * max_pages + pos / prm.P];
+    if (page < 0 || (int64_t)page * prm.P >= prm.num_slots) return;
+    put_token<EB>(prm, page, pos % prm.P, g, c, kb16, vb16);
 }
 
 }  // namespace

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         early1 = bt[min(early_s0 * NPS + 64 + lane, prm.max_pages - 1)];
     }
 
-    const int L = prm.seq_lens[b];
+    const int L = bounded_len(prm.seq_lens[b], prm.max_len);
     const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
     const int a0 = lo & ~63;
     const int c_first = cgrp * prm.chunks_per_group;   // first chunk of this workgroup
@@ -199,6 +199,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                     ids0 = bt[min(max(pbase + lane, pmin), pmax)];
                     ids1 = bt[min(max(pbase + 64 + lane, pmin), pmax)];
                 }
+                ids0 = bounded_page(ids0, prm.num_pages);
+                ids1 = bounded_page(ids1, prm.num_pages);
                 auto page_id = [&](int idx) -> int {   // idx: page index relative to pbase, < 128
                     if constexpr (NPS == 1) {
                         const int a = __builtin_amdgcn_readlane(ids0, idx & 63);
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                 // that the block-table read it needs overlaps with them.  The writes and the later
                 // loads of the same bytes belong to this one wave and are kept in program order by
                 // the hardware; the explicit wait covers the case where that step is the first one.
-                if (gs == s0 && prm.k_new != nullptr && s1 > ((L - 1) >> 6) && j1 == L) {
+                if (gs == s0 && prm.k_new != nullptr && s1 > ((L - 1) >> 6) && j1 == L && prm.seq_lens[b] == L) {
                     const int pos = L - 1;
                     const int64_t page = bt[pos / P];
                     const int off = pos % P;
@@ -257,7 +259,9 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                     const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
                     uint8_t *kd = prm.k + (((page * prm.cache_heads + gc) * P + off) * 64 + lane) * EB;
                     uint8_t *vd = prm.v + (((page * prm.cache_heads + gc) * 64 + lane) * P + off) * EB;
-                    if constexpr (EB == 1) {
+                    if (page < 0 || page >= prm.num_pages) {
+                        // a page the cache does not have: nothing is written
+                    } else if constexpr (EB == 1) {
                         *kd = (uint8_t)quant_one(kb16, prm.k_scale);
                         *vd = (uint8_t)quant_one(vb16, prm.v_scale);
                     } else {
@@ -413,7 +417,7 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
 #pragma unroll
         for (int u = 0; u < NB; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
         if (first && prm.seq_lens != nullptr) {        // chunks past this bound were never written
-            const int L = prm.seq_lens[b];
+            const int L = bounded_len(prm.seq_lens[b], 1 << 30);   // keeps the sums below in 32 bits
             const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
             const int span = L - (lo & ~63);
             n = min(S, (span + prm.split_tokens - 1) / prm.split_tokens);

@@ -44,9 +44,10 @@ __device__ __forceinline__ int wave_inclusive_scan_int(int x) {
     return x;
 }
 
-// The stated budget is three waves per SIMD (170 registers); the kernel needs 126 for FP8 caches with
-// 64-token pages and then runs four per SIMD.  Asking for four makes the compiler schedule for
-// register pressure and spill in the run set-up, which cost 10 %.
+// The stated budget is three waves per SIMD (170 registers); the kernel takes 133 for FP8 caches with
+// 64-token pages.  Asking for four waves (128 registers) makes the compiler schedule for register
+// pressure and spill in the run set-up, which cost 10 %; the shares are planned for one wave per
+// SIMD anyway.
 template <int P, int EB>
 __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
@@ -117,10 +118,10 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     int b = 0, c = 0, L_first = 0;
     {
         // all lengths equal and full: the guess above is the answer, no sums needed
-        const int L0 = prm.seq_lens[0];
+        const int L0 = bounded_len(prm.seq_lens[0], prm.max_len);
         bool uniform = spec_b >= 0 && chunks_of(L0) == prm.n_splits;
         for (int base = 0; base < prm.B && uniform; base += 64) {
-            const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : L0;
+            const int L = (base + lane < prm.B) ? bounded_len(prm.seq_lens[base + lane], prm.max_len) : L0;
             uniform = __ballot(L != L0) == 0;
         }
         if (uniform) {
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         }
     }
     for (int base = 0; base < prm.B && !found; base += 64) {
-        const int L = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
+        const int L = (base + lane < prm.B) ? bounded_len(prm.seq_lens[base + lane], prm.max_len) : 0;
         const int nn = chunks_of(L);
         const int incl = wave_inclusive_scan_int(nn);
         if (base == 0) {
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         for (int base = 0; base < prm.B; base += 64) {
             int len = len0, nn = nn0, incl = incl0;
             if (base > 0) {
-                len = (base + lane < prm.B) ? prm.seq_lens[base + lane] : 0;
+                len = (base + lane < prm.B) ? bounded_len(prm.seq_lens[base + lane], prm.max_len) : 0;
                 nn = chunks_of(len);
                 incl = wave_inclusive_scan_int(nn);
             }
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         const int nb = chunks_of(L);
         if (c >= nb) {                                 // sequence used up (or without chunks): next one
             if (++b >= prm.B) break;                   // cannot happen while chunks remain; keeps the loop finite
-            L = prm.seq_lens[b];
+            L = bounded_len(prm.seq_lens[b], prm.max_len);
             c = 0;
             continue;
         }
@@ -304,6 +305,8 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 ids0 = bt[min(max(pbase + lane, pmin), pmax)];
                 ids1 = bt[min(max(pbase + 64 + lane, pmin), pmax)];
             }
+            ids0 = bounded_page(ids0, prm.num_pages);
+            ids1 = bounded_page(ids1, prm.num_pages);
             auto page_id = [&](int idx) -> int {       // idx: page index relative to pbase, < 128
                 if constexpr (NPS == 1) {
                     const int a = __builtin_amdgcn_readlane(ids0, idx & 63);
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
             load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
             // Fused append (see pz_attn.hip): the run that reaches position L - 1 writes the newest
             // token's K/V (lane = channel) after its first loads are on their way.
-            if (gs == s0 && prm.k_new != nullptr && j1 == L) {
+            if (gs == s0 && prm.k_new != nullptr && j1 == L && prm.seq_lens[b] == L) {
                 const int pos = L - 1;
                 const int64_t page = bt[pos / P];
                 const int off = pos % P;
@@ -358,7 +361,9 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
                 uint8_t *kd = prm.k + (((page * prm.cache_heads + gc) * P + off) * 64 + lane) * EB;
                 uint8_t *vd = prm.v + (((page * prm.cache_heads + gc) * 64 + lane) * P + off) * EB;
-                if constexpr (EB == 1) {
+                if (page < 0 || page >= prm.num_pages) {
+                    // a page the cache does not have: nothing is written
+                } else if constexpr (EB == 1) {
                     *kd = (uint8_t)quant_one(kb16, prm.k_scale);
                     *vd = (uint8_t)quant_one(vb16, prm.v_scale);
                 } else {

@@ -178,6 +178,12 @@ __device__ __forceinline__ void mask_v(VTile<EB> &tile, unsigned valid) {
 }
 
 // 16-bit validity mask of a lane's positions [pos0, pos0 + 16) against [j0, j1)
+// Device-side inputs are held to what the caller sized: a page id from the block table to the pages
+// the cache has, a sequence length to what a block-table row covers.  Inputs outside these bounds are
+// the caller's mistake and give meaningless rows, but no access leaves the cache or the table.
+__device__ __forceinline__ int bounded_page(int id, int num_pages) { return min(max(id, 0), num_pages - 1); }
+__device__ __forceinline__ int bounded_len(int L, int max_len) { return min(L, max_len); }
+
 __device__ __forceinline__ unsigned valid_mask(int pos0, int j0, int j1) {
     int a = min(max(j0 - pos0, 0), 16), b = min(max(j1 - pos0, 0), 16);
     return ((1u << b) - 1u) & ~((1u << a) - 1u);

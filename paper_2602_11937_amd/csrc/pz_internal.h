@@ -31,6 +31,9 @@ struct AttnParams {
     // the host (n_act shares; the first r hold q + 1 chunks, the others q)
     uint32_t full_n_act, full_q, full_r;
     int32_t park;                // balanced kernel: LDS records (partials a wave parks before a write-out)
+    // what device-side inputs are held to, so that no access leaves the cache or a block-table row whatever
+    // they contain: lengths are cut to max_len = max_pages * page_size, page ids to [0, num_pages)
+    int32_t num_pages, max_len;
     float sc;                    // sm_scale * k_scale * log2(e)
     float v_scale;
 };
@@ -75,6 +78,7 @@ struct AppendParams {
     const uint16_t *v_new;
     const int64_t *slot_mapping; // [T]
     int64_t T;
+    int64_t num_slots;           // num_pages * P: tokens whose slot is not in [0, num_slots) are skipped
     int32_t Hkv, P;
     float k_scale, v_scale;
 };
@@ -94,6 +98,7 @@ struct PrefillParams {
     void *out;                   // [T][Hq][64]
     int32_t max_pages, B, Hq, Hkv, G, window, out_dtype, tiles_per_seq;   // Hkv, G: virtual heads as in AttnParams
     int32_t cache_heads, head_shift, G_full;
+    int32_t num_pages, max_len;  // bounds for page ids and lengths, as in AttnParams
     float sc, v_scale;
 };
 

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
     const int q0 = prm.q_start[b], n_new = prm.q_start[b + 1] - q0;
     const int i0 = tile * QT;
     if (i0 >= n_new) return;
-    const int L = prm.seq_lens[b];
+    const int L = bounded_len(prm.seq_lens[b], prm.max_len);
     const int W = prm.window;
 
     // this lane's column in column tile u: query token i0 + 2u + (n >> 3), head n & 7
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(64, 2) void prefill_attn_kernel(const pz::PrefillPa
     for (int gs = s0; gs < s1; gs += GROUP) {
         const int ge = min(gs + GROUP, s1);
         const int pbase = gs * NPS;
-        const int ids = bt[min(max(pbase + lane, pmin), pmax)];
+        const int ids = bounded_page(bt[min(max(pbase + lane, pmin), pmax)], prm.num_pages);
         auto page_id = [&](int idx) -> int {
             if constexpr (NPS == 1) return __builtin_amdgcn_readlane(ids, idx);
             else return __shfl(ids, idx);

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void rope_kv_append_kernel(const pz::RopeAppen
             rotate8(prm.ap.k_new + (t * Hkv + g) * 64, prm.cos_tab + (int64_t)pos * 32, prm.sin_tab + (int64_t)pos * 32,
                     part, o1, o2);
             const int64_t slot = prm.ap.slot_mapping[t];
-            if (slot >= 0) {
+            if (slot >= 0 && slot < prm.ap.num_slots) {
                 const int64_t page = slot / P, off = slot % P;
                 uint8_t *dst = prm.ap.k + (((page * Hkv + g) * P + off) * 64) * EB;
                 if constexpr (EB == 1) {
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void rope_kv_append_kernel(const pz::RopeAppen
             const u32x4 x0 = reinterpret_cast<const u32x4 *>(src)[0];
             const u32x4 x1 = reinterpret_cast<const u32x4 *>(src)[1];
             const int64_t slot = prm.ap.slot_mapping[tv];
-            if (slot >= 0) {
+            if (slot >= 0 && slot < prm.ap.num_slots) {
                 const int64_t page = slot / P, off = slot % P;
                 uint8_t *dst = prm.ap.v + (((page * Hkv + g) * 64 + c0) * P + off) * EB;
 #pragma unroll

@@ -76,6 +76,11 @@ def test_decode_attn_rejects_bad_arguments_before_any_launch():
     assert attn(cache(), split_tokens=128, n_splits=2, workspace=0x50, workspace_bytes=100) == WS
     assert attn(cache(), split_tokens=128, n_splits=0, workspace=0x50, workspace_bytes=1 << 30) == SHAPE
     assert attn(cache(), out_dtype=3) == UNSUP
+    # positions are 32-bit inside the kernels: a block-table row of more than 2^30 positions and
+    # chunk grids that reach past 2^31 positions are refused
+    assert attn(cache(page_size=64), max_pages=(1 << 24) + 1) == UNSUP
+    assert attn(cache(page_size=16), max_pages=1 << 26, batch=0) == 0
+    assert attn(cache(), split_tokens=1 << 20, n_splits=2048, workspace=0x50, workspace_bytes=1 << 40) == UNSUP
     assert attn(cache(), batch=0) == 0                               # nothing to do is not an error
 
 
@@ -121,6 +126,7 @@ def test_append_and_reduce_reject_bad_arguments():
     assert red(ws=None) == -4 and red(wsb=10) == -4
     assert red(out=None) == -1 and red(d=128) == -3 and red(S=0) == -2
     assert red(seq_lens=0x30, split=0) == -2 and red(vs=0.0) == -2
+    assert red(seq_lens=0x30, split=(1 << 30) + 64) == -3
     assert red(batch=0) == 0
 
 
@@ -159,6 +165,7 @@ def test_new_entry_points_reject_bad_arguments():
     assert pre(c, hq=60) == -2 and pre(c, mx=-1) == -2 and pre(c, sm=0.0) == -2
     assert pre(cache(n_kv_heads=1), hq=65) == -3 and pre(c, odt=5) == -3    # a group of 65 heads
     assert pre(c, b=0) == 0 and pre(c, mx=0) == 0
+    assert pre(cache(page_size=64), mp=(1 << 24) + 1) == -3                 # more than 2^30 positions per row
     # page pool
     assert lib.pz_page_pool_create(4, 16, 1, 0, 0) is None
     assert lib.pz_page_pool_append(None, 0) == -1 and lib.pz_page_pool_free_pages(None) == -1
