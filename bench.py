@@ -58,6 +58,8 @@ WORKLOADS = {
     # diagnostics: uniform lengths at twice cfg3's batch, and cfg3's batch with ragged lengths
     "diag_b32_uniform": dict(B=32, L=65536, window=0, split_tokens=1024, outlier_frac=0.0, seed=7, instances=3,
                              text="diagnostic: batch 32 x context 65536, split-K 1024"),
+    "diag_b40_uniform": dict(B=40, L=65536, window=0, split_tokens=1024, outlier_frac=0.0, seed=9, instances=2,
+                             text="diagnostic: batch 40 x context 65536, split-K 1024 (20 chunks per SIMD-wave)"),
     "diag_b8_128k": dict(B=8, L=131072, window=0, split_tokens=1024, outlier_frac=0.0, seed=8, instances=4,
                          text="diagnostic: batch 8 x context 131072, split-K 1024"),
     "diag_b16_ragged": dict(B=16, L=(1024, 131072), window=0, split_tokens=1024, outlier_frac=0.0, seed=5, instances=4,

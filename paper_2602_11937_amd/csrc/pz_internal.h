@@ -43,17 +43,22 @@ hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int
 // Balanced partition of `tot` chunks of one KV head over at most `bph` workgroups: n_act shares, the
 // first r of q + 1 chunks, the others of q.  The share size aimed at is the smallest that leaves at
 // most 1024 waves over all heads -- one per SIMD, four per CU; measured best on this chip, ahead of
-// twice or four times as many shorter shares and far ahead of counts that fill the CUs unevenly --
-// but at most 16 chunks; it grows past that only when the grid is capped.  With k = q + 1 (or q when
-// r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ are the smaller ones.
+// twice or four times as many shorter shares and far ahead of counts that fill the CUs unevenly.
+// Never more than 1024 shares in all: a workgroup that parks 13 to 16 partials takes a quarter of a
+// CU's LDS, so only 1024 of them are resident and a few shares beyond that would run as a second
+// round after the first (batch 40 x 64K with shares held to 16 chunks: 586 us against 429 us).  With
+// k = q + 1 (or q when r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ
+// are the smaller ones.
 __host__ __device__ inline unsigned balanced_want(unsigned tot, unsigned n_heads) {
     const unsigned want = (tot * n_heads + 1023u) / 1024u;
-    return want < 1u ? 1u : (want > 16u ? 16u : want);
+    return want < 1u ? 1u : want;
 }
 __host__ __device__ inline void balanced_plan(unsigned tot, unsigned n_heads, unsigned bph, unsigned *n_act,
                                               unsigned *q, unsigned *r) {
     const unsigned want = balanced_want(tot, n_heads);
     unsigned cap = (tot + want - 1u) / want;
+    const unsigned simds_per_head = n_heads >= 1024u ? 1u : 1024u / n_heads;
+    if (cap > simds_per_head) cap = simds_per_head;    // head counts that do not divide 1024
     if (cap > bph) cap = bph;
     const unsigned k = (tot + cap - 1u) / cap;
     *n_act = (tot + k - 1u) / k;

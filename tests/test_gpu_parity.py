@@ -361,6 +361,26 @@ def test_balanced_partition_over_many_ragged_sequences(B, max_len, split, monkey
     assert rel_err(avg_g, avg_o) <= TOL
 
 
+@pytest.mark.parametrize("B,Hq,Hkv", [(8, 8, 2), (6, 6, 3)])
+def test_balanced_partition_shares_longer_than_the_lds_records(B, Hq, Hkv):
+    """So many chunks that a share of one wave per SIMD holds more than the 16 partials a workgroup parks
+    in LDS (written out in several goes), also with a head count that does not divide the SIMD count."""
+    rng = np.random.default_rng(B * Hkv)
+    lens = rng.integers(50000, 131073, size=B)
+    lens[0] = 131072
+    split = 64
+    assert sum(-(-int(L) // split) for L in lens) * Hkv > 18 * 1024
+    case = wl.make_case("long_shares", B=B, Hq=Hq, Hkv=Hkv, d=64, P=64, seq_lens=lens.tolist(), seed=B)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    want = oracle_attn(case, kc, vc, accum="f64")
+    got, acc, ml = gpu_attn(case, cache, split_tokens=split, return_ws=True)
+    assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL
+    for b in range(B):
+        n_b = -(-int(lens[b]) // split)
+        assert np.all(np.isfinite(ml[b, :, :n_b])) and np.all(np.isnan(ml[b, :, n_b:]))
+
+
 def test_balanced_partition_degenerate_batches(monkeypatch):
     """No chunk at all (every sequence empty), a single sequence, and one chunk for the whole batch."""
     monkeypatch.setenv("PZ_ATTN_WAVES", "1")
