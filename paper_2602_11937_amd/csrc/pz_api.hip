@@ -243,7 +243,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     // comparisons).  Window layers keep that grid: their sequences all span about the window, their
     // first and last chunks are short, which a partition by chunk count does not see, and a share that
     // crosses from one short sequence into the next starts its pipeline anew each time (batch 256,
-    // window 8192: 504 us on the balanced partition against 362 us on the grid).
+    // window 8192: 373 us on the balanced partition against 355 us on the grid).
     if (split_tokens > 0 && window == 0 && n_waves == 1 && !env_is_zero("PZ_ATTN_BALANCED"))
         e = pz::launch_decode_attn_balanced(p, cache->page_size, elem_bytes, static_cast<hipStream_t>(hip_stream));
     else
