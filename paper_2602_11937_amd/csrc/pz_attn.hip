@@ -287,8 +287,9 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         }
         // burst the parked partials out: 16 lanes cover one 256-byte row, a wave-wide store covers
         // 4 rows.  The stores are non-temporal: the partials are read once, by another kernel, and
-        // written through they do not wait in L2 for the write-back at the end of the kernel.  Chunks of the group that lie beyond the context were never parked and are not
-        // written: the merge kernel bounds its reads by the sequence length.
+        // written through they do not wait in L2 for the write-back at the end of the kernel.
+        // Chunks of the group that lie beyond the context were never parked and are not written:
+        // the merge kernel bounds its reads by the sequence length.
         __syncthreads();                               // lanes read what other lanes parked
         const int n_rows = (next_chunk - c_first) * G;
         const int quad = lane & 15;
