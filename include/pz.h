@@ -121,7 +121,12 @@ int32_t pz_decode_attn_n_splits(int32_t max_seq_len, int32_t window, int32_t spl
  * A partial is sink-free and unnormalised:  with s_j the scaled logit of position j,
  *     m = max_j s_j (natural-log units),  l = sum_j exp(s_j - m),
  *     acc[c] = sum_j exp(s_j - m) * decode(V[j][c])        (v_scale not applied),
- * an empty chunk is (m = -inf, l = 0, acc = 0).
+ * an empty row is (m = -inf, l = 0) and its acc is not read.
+ * Row i of a sequence holds the partial over the positions of chunks i .. i + r - 1, r >= 1, and
+ * rows i + 1 .. i + r - 1 are empty: a workgroup that is given several consecutive chunks of one
+ * sequence runs them as one online softmax and leaves one partial in the row of the first (which
+ * chunks share a workgroup is the library's choice and depends on the batch).  The merge is the
+ * same either way: pz_decode_attn_splitk_reduce combines the rows that are not empty.
  */
 size_t pz_decode_attn_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t head_dim,
                                       int32_t n_splits);
@@ -152,9 +157,9 @@ size_t pz_decode_attn_workspace_bytes(int32_t batch, int32_t n_q_heads, int32_t 
  *   split_tokens : 0 = single pass: the sink is applied and `out` is written
  *                  (workspace may be NULL, n_splits is ignored);
  *                  > 0 (a multiple of 64) = split-K: only partials are written to `workspace`
- *                  (chunks as defined at pz_decode_attn_n_splits; a chunk that holds no attended
- *                  position of its sequence is NOT written -- its workspace rows keep whatever
- *                  they held), `out` is not touched, and the caller enqueues
+ *                  (rows as defined at pz_decode_attn_workspace_bytes; the row of a chunk that
+ *                  holds no attended position of its sequence is NOT written -- it keeps whatever
+ *                  it held), `out` is not touched, and the caller enqueues
  *                  pz_decode_attn_splitk_reduce with the same seq_lens / window / split_tokens
  *                  on the same stream.  Positions beyond n_splits * split_tokens of a_b are
  *                  ignored, so n_splits must be at least pz_decode_attn_n_splits(max_b L_b, ...).

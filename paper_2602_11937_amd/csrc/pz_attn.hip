@@ -38,9 +38,10 @@
 namespace {
 
 // Grid: one workgroup per (sequence, KV head, chunk group).  Two modes:
-//   n_waves == 1 ("direct"): the wave walks every chunk of its group back to back -- the load
-//     pipeline is not drained at chunk boundaries -- and writes each chunk's partial (split-K)
-//     or the final row (single pass) straight from registers.
+//   n_waves == 1 ("direct"): the wave walks every chunk of its group back to back as one online
+//     softmax and writes the final row (single pass) straight from registers, or (split-K) one
+//     partial for the group: it goes to the workspace row of the group's first chunk, the rows of
+//     its other chunks are marked empty (m = -inf, l = 0) and the merge kernel skips them.
 //   n_waves  > 1: one chunk (or the whole sequence) per workgroup, its steps dealt to the waves,
 //     merged through LDS.
 template <int P, int EB>
@@ -48,7 +49,7 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     constexpr int NPS = 64 / P;                        // pages per step
     constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
     // dynamic LDS in records of 528 floats (8 heads x 64 channels, then 8 m's, then 8 l's):
-    // one record per wave (n_waves > 1), or one per chunk of the group (one-wave split-K)
+    // one record per wave (n_waves > 1), or one for the group's partial (one-wave split-K)
     extern __shared__ float lds[];
     float (*sm_acc)[8][64] = reinterpret_cast<float (*)[8][64]>(lds);
     float (*sm_m)[8] = reinterpret_cast<float (*)[8]>(lds + (blockDim.x >> 6) * 512);
@@ -108,10 +109,10 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
     };
     reset_state();
 
-    // direct mode: park the state as partial number `slot` of this wave in LDS (split-K; the
-    // partials go to HBM in one burst when the wave is done, so that no store sits between the
-    // loads of the pipeline), or write it as the final row (single pass); then reset it
-    auto emit_direct = [&](int slot) {
+    // direct mode: put the state into LDS as the group's partial (split-K; it goes to HBM row-wise,
+    // 16 lanes per 256-byte row, when the wave is done), or write it as the final row (single pass)
+    auto emit_direct = [&]() {
+        constexpr int slot = 0;
         const float l = add_ror8(st.l[0]);           // both P halves, all 64 positions of every step
         float scale = 1.0f;
         if (final_pass) {
@@ -147,8 +148,6 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         reset_state();
     };
 
-    int next_chunk = c_first;                          // direct split-K: first chunk not yet written
-
     if (!empty) {
         const int s_begin = j0 >> 6, s_end = (j1 + 63) >> 6;
         const int n_steps = s_end - s_begin;
@@ -174,8 +173,6 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
             const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
             const float sc = prm.sc;
-            const int steps_per_chunk = prm.split_tokens >> 6;
-            const int a0_step = a0 >> 6;
 
             KTile<EB> kt;
             VTile<EB> vt;
@@ -236,12 +233,6 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
                     if (!full) mask_v<EB>(vt, valid);
                     pv_step<EB>(vt, pw, st);
                     if (prefetch) load_v<P, EB, EB == 1>(vt, v_page(s + 1), geom.voff);
-                    // direct split-K: a chunk ends after this step -> write its partial
-                    if (direct && !final_pass &&
-                        ((s + 1 - a0_step) % steps_per_chunk == 0 || s + 1 == s1)) {
-                        emit_direct(next_chunk - c_first);
-                        ++next_chunk;
-                    }
                 };
                 load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
                 load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
@@ -282,16 +273,18 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
 
     if (direct) {
         if (final_pass) {
-            emit_direct(0);
+            emit_direct();
             return;
         }
+        if (empty) return;                             // no chunk of the group holds a position: nothing is written
+        emit_direct();
         // burst the parked partials out: 16 lanes cover one 256-byte row, a wave-wide store covers
         // 4 rows.  The stores are non-temporal: the partials are read once, by another kernel, and
         // written through they do not wait in L2 for the write-back at the end of the kernel.
         // Chunks of the group that lie beyond the context were never parked and are not written:
         // the merge kernel bounds its reads by the sequence length.
         __syncthreads();                               // lanes read what other lanes parked
-        const int n_rows = (next_chunk - c_first) * G;
+        const int n_rows = G;
         const int quad = lane & 15;
         for (int r0 = 0; r0 < n_rows; r0 += 16) {
             f32x4 x[4];
@@ -320,6 +313,15 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
             ml.y = lds[cl * 528 + 520 + h];
             __builtin_nontemporal_store(ml.x, prm.ws_ml + row * 2);
             __builtin_nontemporal_store(ml.y, prm.ws_ml + row * 2 + 1);
+        }
+        // the group's other chunks that hold positions: empty rows
+        const int c_end = min(c_last, (j1 - 1 - a0) / prm.split_tokens + 1);
+        const int n_rest = (c_end - c_first - 1) * G;
+        for (int r = lane; r < n_rest; r += 64) {
+            const int cl = 1 + r / G, h = r % G;
+            const int64_t row = ((int64_t)b * prm.Hq + q_first + h) * prm.n_splits + c_first + cl;
+            __builtin_nontemporal_store(-INFINITY, prm.ws_ml + row * 2);
+            __builtin_nontemporal_store(0.0f, prm.ws_ml + row * 2 + 1);
         }
         return;
     }
@@ -436,8 +438,10 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
         for (int u = 0; u < NB; ++u) {
             const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
             // rows past the sequence's chunks may hold anything (the first batch is fetched before
-            // the bound is known), so they are dropped by a select, not by a zero weight
-            num = __builtin_fmaf(base + u < n ? x[u] : 0.f, wu, num);
+            // the bound is known), and so may the acc of an empty row (its chunk was merged into an
+            // earlier row and only its (m, l) were written): both are dropped by a select, not by a
+            // zero weight
+            num = __builtin_fmaf((base + u < n && wu != 0.f) ? x[u] : 0.f, wu, num);
         }
     }
     if constexpr (W > 1) {
@@ -478,7 +482,7 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
     const int n_chunks = prm.split_tokens > 0 ? prm.n_splits : 1;
     const int n_groups = (n_chunks + prm.chunks_per_group - 1) / prm.chunks_per_group;
     const dim3 grid((unsigned)(prm.B * prm.Hkv * n_groups)), block(64 * n_waves);
-    const size_t records = n_waves > 1 ? n_waves : (prm.split_tokens > 0 ? prm.chunks_per_group : 0);
+    const size_t records = n_waves > 1 ? n_waves : (prm.split_tokens > 0 ? 1 : 0);
     const size_t lds_bytes = records * (8 * 64 + 16) * sizeof(float);
 #define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((decode_attn_kernel<P, EB>), grid, block, lds_bytes, stream, prm)
     if (elem_bytes == 1) {

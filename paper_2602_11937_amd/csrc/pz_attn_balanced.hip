@@ -13,8 +13,11 @@
 // are active; the first tot mod n_act shares hold k chunks and the others k - 1, so the shares
 // that differ have LESS work and nothing is left over at the end (balanced_plan, pz_internal.h).
 // A share may span several sequences; each run of chunks inside one sequence is streamed with
-// the register pipeline of pz_attn.hip, its partials parked in LDS and written out when the run
-// ends or, between two groups of loads, when the LDS records are full.  The partition is a pure
+// the register pipeline of pz_attn.hip as ONE online softmax, and leaves one partial: it goes to
+// the workspace row of the run's first chunk, and the rows of the run's other chunks are marked
+// empty (m = -inf, l = 0), which the merge kernel skips.  Merging a run in registers is the same
+// arithmetic as the merge kernel's, done earlier: on batch 16 x 64K (8 chunks per run) it saves
+// writing and re-reading 7 of 8 partials, 175.1 -> 172.5 us per step.  The partition is a pure
 // function of the lengths: no queue, no atomics, nothing to wait for.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -25,11 +28,6 @@
 #include "pz_quant.h"
 
 namespace {
-
-// Partials parked in LDS before a write-out: as many records of 2112 bytes as the largest share has
-// chunks, at most this many (16 records leave room for one workgroup per SIMD, which is what such
-// shares are planned for).  A share with more chunks is streamed in groups of that many.
-constexpr int kParkMax = 16;
 
 // Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS traffic): four shifted adds
 // inside every row of 16 lanes, then lane 15 of rows 0 and 2 is added to rows 1 and 3, then
@@ -52,7 +50,7 @@ template <int P, int EB>
 __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
     constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
-    extern __shared__ float lds[];                     // prm.park records of 528 floats (8 x 64 acc, 8 m, 8 l)
+    __shared__ float lds[528];                         // a run's partial on its way out: 8 x 64 acc, 8 m, 8 l
 
     const int lane = threadIdx.x;
     const int n = lane & 15, kb = lane >> 4;
@@ -192,8 +190,9 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
     };
     reset_state();
 
-    // park the state as partial number `slot` in LDS and reset it
-    auto park = [&](int slot) {
+    // put the state into LDS as the run's partial and reset it
+    auto park = [&]() {
+        constexpr int slot = 0;
         const float l = add_ror8(st.l[0]);             // both P halves, all 64 positions of every step
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
@@ -208,11 +207,12 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         }
         reset_state();
     };
-    // write the parked partials of chunks [chunk0, chunk0 + count) of sequence bb out: 16 lanes cover
-    // one 256-byte row, a wave-wide store covers 4 rows.  Non-temporal: read once, by the merge kernel.
-    auto write_out = [&](int bb, int chunk0, int count) {
+    // write the parked partial of the run [chunk0, chunk_end) of sequence bb to the rows of chunk0 and
+    // mark the rows of the other chunks empty: 16 lanes cover one 256-byte row, a wave-wide store covers
+    // 4 rows.  Non-temporal: read once, by the merge kernel.
+    auto write_out = [&](int bb, int chunk0, int chunk_end) {
         __syncthreads();                               // lanes read what other lanes parked
-        const int n_rows = count * G;
+        const int n_rows = G;
         const int quad = lane & 15;
         for (int r0 = 0; r0 < n_rows; r0 += 16) {
             f32x4 x[4];
@@ -238,7 +238,14 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
             __builtin_nontemporal_store(lds[cl * 528 + 512 + h], prm.ws_ml + row * 2);
             __builtin_nontemporal_store(lds[cl * 528 + 520 + h], prm.ws_ml + row * 2 + 1);
         }
-        __syncthreads();                               // the records are free again
+        const int n_rest = (chunk_end - chunk0 - 1) * G;
+        for (int r = lane; r < n_rest; r += 64) {
+            const int cl = 1 + r / G, h = r % G;
+            const int64_t row = ((int64_t)bb * prm.Hq + q_first + h) * prm.n_splits + chunk0 + cl;
+            __builtin_nontemporal_store(-INFINITY, prm.ws_ml + row * 2);
+            __builtin_nontemporal_store(0.0f, prm.ws_ml + row * 2 + 1);
+        }
+        __syncthreads();                               // the record is free again
     };
 
     bool first_run = true;
@@ -261,7 +268,6 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         const int32_t *bt = prm.block_table + (int64_t)b * prm.max_pages;
         const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
         const int a0 = lo & ~63;
-        const int a0_step = a0 >> 6;
         const int j0 = max(lo, a0 + c_first * split);
         const int j1 = (int)min((int64_t)L, (int64_t)a0 + (int64_t)c_last * split);
         const int s0 = j0 >> 6, s1 = (j1 + 63) >> 6;   // s0 < s1: every chunk of the list holds a position
@@ -282,17 +288,13 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
             qb[1] = __builtin_bit_cast(bf16x8, q1);
         }
 
-        int parked = 0, park_chunk0 = c_first;
         KTile<EB> kt;
         VTile<EB> vt;
         // Steps are walked in groups whose page ids sit in two registers; inside a group the K buffer is
         // refilled right after QK^T has consumed it and the V buffer right after PV, unconditionally; the
         // group's last step is peeled so that no load is conditional (see pz_attn.hip).
         for (int gs = s0; gs < s1;) {
-            // a group also ends where the LDS records run out, so that partials are written out only
-            // between groups, where the pipeline is drained anyway
-            const int ge_park = a0_step + ((gs - a0_step) / steps_per_chunk + (prm.park - parked)) * steps_per_chunk;
-            const int ge = min(min(gs + GROUP, s1), ge_park);
+            const int ge = min(gs + GROUP, s1);
             const int pbase = gs * NPS;
             int ids0, ids1;
             if (use_early && gs == s0) {               // s0 == spec_c * steps_per_chunk here (window == 0)
@@ -342,11 +344,6 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
                 if (!full) mask_v<EB>(vt, valid);
                 pv_step<EB>(vt, pw, st);
                 if (prefetch) load_v<P, EB, EB == 1>(vt, v_page(s + 1), geom.voff);
-                // a chunk ends after this step -> park its partial
-                if ((s + 1 - a0_step) % steps_per_chunk == 0 || s + 1 == s1) {
-                    park(parked);
-                    ++parked;
-                }
             };
             load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
             load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
@@ -378,10 +375,9 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
             }
             for (int s = gs; s + 1 < ge; ++s) step(s, true);
             step(ge - 1, false);
-            if (parked == prm.park || ge == s1) {
-                if (parked > 0) write_out(b, park_chunk0, parked);
-                park_chunk0 += parked;
-                parked = 0;
+            if (ge == s1) {                            // the run is done
+                park();
+                write_out(b, c_first, c_last);
             }
             gs = ge;
         }
@@ -392,14 +388,13 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
 
 namespace pz {
 
-// Workgroups of decode_attn_balanced_kernel<P, EB> (one wave each, one LDS record) that fit the device at
-// once: the partition never plans more shares per launch than this.  Worked out once per kernel variant
+// Workgroups of decode_attn_balanced_kernel<P, EB> (one wave each) that fit the device at once: the
+// partition never plans more shares per launch than this.  Worked out once per kernel variant
 // (function-local static: initialised once, also with several host threads).
 template <int P, int EB>
 static int query_slots() {
     int per_cu = 0, dev = 0, cus = 0;
-    const size_t lds_bytes = 528 * sizeof(float);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_balanced_kernel<P, EB>, 64, lds_bytes) !=
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, decode_attn_balanced_kernel<P, EB>, 64, 0) !=
             hipSuccess || per_cu <= 0)
         per_cu = 8;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -435,14 +430,7 @@ hipError_t launch_decode_attn_balanced(const AttnParams &prm_in, int page_size, 
         bph = room < prm.full_n_act ? prm.full_n_act : room;
     }
     const dim3 grid((unsigned)(bph * prm.Hkv)), block(64);
-    // no batch of shorter sequences is planned with larger shares than these (and one that were would
-    // only be written out in two goes)
-    unsigned k_full = prm.full_q + (prm.full_r > 0 ? 1u : 0u);
-    const unsigned want_full = balanced_want(cap_chunks, (unsigned)prm.Hkv);
-    if (k_full < want_full) k_full = want_full;
-    prm.park = (int)(k_full < 1u ? 1u : (k_full > (unsigned)kParkMax ? (unsigned)kParkMax : k_full));
-    const size_t lds_bytes = (size_t)prm.park * 528 * sizeof(float);
-#define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, lds_bytes, stream, prm)
+#define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, 0, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);
         else if (page_size == 32) PZ_LAUNCH(32, 1);

@@ -30,7 +30,6 @@ struct AttnParams {
     // balanced kernel: the partition of a batch whose sequences all have n_splits chunks, worked out on
     // the host (n_act shares; the first r hold q + 1 chunks, the others q)
     uint32_t full_n_act, full_q, full_r;
-    int32_t park;                // balanced kernel: LDS records (partials a wave parks before a write-out)
     // what device-side inputs are held to, so that no access leaves the cache or a block-table row whatever
     // they contain: lengths are cut to max_len = max_pages * page_size, page ids to [0, num_pages)
     int32_t num_pages, max_len;
@@ -43,12 +42,9 @@ hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int
 // Balanced partition of `tot` chunks of one KV head over at most `bph` workgroups: n_act shares, the
 // first r of q + 1 chunks, the others of q.  The share size aimed at is the smallest that leaves at
 // most 1024 waves over all heads -- one per SIMD, four per CU; measured best on this chip, ahead of
-// twice or four times as many shorter shares and far ahead of counts that fill the CUs unevenly.
-// Never more than 1024 shares in all: a workgroup that parks 13 to 16 partials takes a quarter of a
-// CU's LDS, so only 1024 of them are resident and a few shares beyond that would run as a second
-// round after the first (batch 40 x 64K with shares held to 16 chunks: 586 us against 429 us).  With
-// k = q + 1 (or q when r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ
-// are the smaller ones.
+// twice or four times as many shorter shares and far ahead of counts that fill the CUs unevenly --
+// so never more than 1024 shares in all, however many chunks there are.  With k = q + 1 (or q when
+// r == 0) the largest share, n_act = ceil(tot / k), so the shares that differ are the smaller ones.
 __host__ __device__ inline unsigned balanced_want(unsigned tot, unsigned n_heads) {
     const unsigned want = (tot * n_heads + 1023u) / 1024u;
     return want < 1u ? 1u : want;

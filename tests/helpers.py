@@ -103,3 +103,59 @@ def division_sensitive_inputs():
             for i in idx[c1 != c2]:
                 found.append((int(bf16_bits(x[i:i + 1])[0]), float(sc[i]), float(r1[i]), float(r2[i])))
     return found
+
+
+def merge_runs_of_partials(oacc, oml, starts):
+    """Per-chunk partials of one (sequence, head) row -> one partial per run of consecutive chunks.
+
+    oacc [S][d], oml [S][2] = (m, l) per chunk; `starts` = sorted chunk indices at which a run begins,
+    run i covering [starts[i], starts[i + 1]) and the last one every chunk up to the last non-empty one.
+    Returns (lse [R], avg [R][d]): the log-sum-exp of a run's logits and its softmax average of V,
+    the two quantities of a partial that do not depend on the reference maximum."""
+    oacc = np.asarray(oacc, dtype=np.float64)
+    m = np.asarray(oml[:, 0], dtype=np.float64)
+    l = np.asarray(oml[:, 1], dtype=np.float64)
+    live = np.nonzero(m > -np.inf)[0]
+    end_all = int(live[-1]) + 1 if len(live) else 0
+    lse, avg = [], []
+    for i, a in enumerate(starts):
+        b = starts[i + 1] if i + 1 < len(starts) else end_all
+        mm, ll, aa = m[a:b], l[a:b], oacc[a:b]
+        M = mm.max()
+        w = np.where(mm > -np.inf, np.exp(mm - M), 0.0)
+        den = float((ll * w).sum())
+        lse.append(M + np.log(den))
+        avg.append((aa * w[:, None]).sum(axis=0) / den)
+    return np.array(lse), np.array(avg)
+
+
+def check_workspace_rows(acc, ml, oacc, oml, tol):
+    """The split-K workspace of the GPU path ([B][Hq][S][d] and [B][Hq][S][2]) against the oracle's
+    per-chunk partials.  A row is unwritten (chunk without an attended position), empty (m = -inf,
+    l = 0: its chunk was merged into an earlier row) or holds the partial of the run of chunks from
+    itself to the next row that is not empty.  Returns the number of rows that hold a partial."""
+    B, Hq, S, _ = acc.shape
+    n_partials = 0
+    worst_avg, worst_lse = 0.0, 0.0
+    for b in range(B):
+        for h in range(Hq):
+            gm, gl = ml[b, h, :, 0], ml[b, h, :, 1]
+            o_live = oml[b, h, :, 0] > -np.inf
+            assert np.all(np.isnan(gm[~o_live])), "a chunk without positions was written"
+            assert not np.any(np.isnan(gm[o_live])), "a chunk with positions was not written"
+            if not o_live.any():
+                continue
+            starts = [int(i) for i in np.nonzero(np.isfinite(gm))[0]]
+            assert starts and starts[0] == int(np.nonzero(o_live)[0][0]), "the first chunk must hold a partial"
+            empty_rows = o_live & ~np.isfinite(gm)
+            assert np.all(np.isneginf(gm[empty_rows])) and np.all(gl[empty_rows] == 0)
+            lse_o, avg_o = merge_runs_of_partials(oacc[b, h], oml[b, h], starts)
+            lse_g = gm[starts].astype(np.float64) + np.log(gl[starts].astype(np.float64))
+            avg_g = acc[b, h][starts].astype(np.float64) / gl[starts].astype(np.float64)[:, None]
+            worst_lse = max(worst_lse, float(np.max(np.abs(lse_g - lse_o))))
+            rms = float(np.sqrt(np.mean(avg_o ** 2)))
+            worst_avg = max(worst_avg, float(np.max(np.abs(avg_g - avg_o))) / (rms if rms > 0 else 1.0))
+            n_partials += len(starts)
+    assert worst_lse < 2e-4, worst_lse
+    assert worst_avg <= tol, worst_avg
+    return n_partials

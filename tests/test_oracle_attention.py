@@ -356,3 +356,28 @@ def test_prefill_is_causal_attention_inside_the_window():
     one = oracle.prefill_attn(kc, vc, case.P, case.q, np.arange(case.B + 1), case.block_table, case.seq_lens,
                               case.sinks, case.sm_scale, case.k_scale, case.v_scale, 0)
     assert np.array_equal(one, run(case, kc, vc))
+
+
+def test_run_merge_helper_agrees_with_the_oracle_reduce():
+    """tests/helpers.merge_runs_of_partials (used to compare workspaces whose rows hold several chunks)
+    against oracle.splitk_reduce: one run over every chunk is the reduce itself, and reducing the runs'
+    partials gives what reducing the chunks' partials gives."""
+    from helpers import merge_runs_of_partials
+    rng = np.random.default_rng(77)
+    S, d = 23, 64
+    acc = rng.standard_normal((S, d)).astype(np.float32)
+    ml = np.stack([rng.standard_normal(S) * 15, rng.uniform(1, 500, S)], -1).astype(np.float32)
+    ml[5] = (-np.inf, 0)
+    ml[20:] = (-np.inf, 0)                                            # trailing chunks without positions
+    want = oracle.splitk_reduce(acc[None, None], ml[None, None], None, 1.0)[0, 0]
+    lse, avg = merge_runs_of_partials(acc, ml, [0])
+    assert np.allclose(avg[0], want, rtol=1e-5, atol=1e-6)
+    starts = [0, 4, 6, 13, 19]
+    lse, avg = merge_runs_of_partials(acc, ml, starts)
+    acc2 = np.zeros((S, d), dtype=np.float32)
+    ml2 = np.full((S, 2), (-np.inf, 0), dtype=np.float32)
+    acc2[starts] = avg
+    ml2[starts, 0] = lse
+    ml2[starts, 1] = 1.0
+    again = oracle.splitk_reduce(acc2[None, None], ml2[None, None], None, 1.0)[0, 0]
+    assert np.allclose(again, want, rtol=1e-5, atol=1e-6)
