@@ -34,7 +34,7 @@ import numpy as np  # noqa: E402
 
 # HBM bytes per decode_attn launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (profiles/decode_step_cfg3_fp8_hbm_traffic.txt:
 # counters scaled by what they read for a plain 768 MiB copy); only measured for the default cfg3 launch.
-MEASURED_TRAFFIC_BYTES = {"cfg3": 1092793869}
+MEASURED_TRAFFIC_BYTES = {"cfg3": 1078362834}
 
 METRIC = "decode-attention GB/s (% of HBM peak) + attn tokens/s, B=16 ctx=64K FP8 KV"
 HBM_PEAK_GBPS = 8000.0
