@@ -389,6 +389,28 @@ def test_balanced_partition_with_long_shares(B, Hq, Hkv):
         assert not np.any(np.isnan(ml[b, :, :n_b])) and np.all(np.isnan(ml[b, :, n_b:]))
 
 
+@pytest.mark.parametrize("B,expected_runs", [(130, 1), (70, 3), (32, 6)])
+def test_window_split_groups_of_chunks(B, expected_runs):
+    """Window layers with enough (sequence, KV head) pairs that a one-wave workgroup walks several chunks:
+    the whole window (130 sequences x 8 heads fill the SIMDs) or pairs of chunks; with few pairs a chunk
+    is dealt to several waves and every chunk has its partial.  A window of 300 positions in 64-token
+    chunks is 4 whole chunks and up to two short ones."""
+    rng = np.random.default_rng(B)
+    lens = rng.integers(1, 900, size=B)
+    lens[:3] = (899, 300, 64)
+    case = wl.make_case("wg", B=B, Hq=8, Hkv=8, d=64, P=64, seq_lens=lens.tolist(), window=300, seed=B)
+    cache = gpu_cache(case)
+    kc, vc = oracle_cache(case)
+    want = oracle_attn(case, kc, vc, accum="f64")
+    got, acc, ml = gpu_attn(case, cache, split_tokens=64, return_ws=True)
+    assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL
+    oacc, oml = oracle.decode_attn_partials(kc, vc, case.P, case.q, case.block_table, case.seq_lens, case.sm_scale,
+                                            case.k_scale, 300, 64, ml.shape[2], accum="f64", nthreads=8)
+    check_workspace_rows(acc, ml, oacc, oml, TOL)
+    # the longest sequence: its 6 chunks form the expected number of runs
+    assert int(np.isfinite(ml[0, 0, :, 0]).sum()) == expected_runs
+
+
 def test_balanced_partition_degenerate_batches(monkeypatch):
     """No chunk at all (every sequence empty), a single sequence, and one chunk for the whole batch."""
     monkeypatch.setenv("PZ_ATTN_WAVES", "1")
