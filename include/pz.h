@@ -121,7 +121,7 @@ int32_t pz_decode_attn_n_splits(int32_t max_seq_len, int32_t window, int32_t spl
  * A partial is sink-free and unnormalised:  with s_j the scaled logit of position j,
  *     m = max_j s_j (natural-log units),  l = sum_j exp(s_j - m),
  *     acc[c] = sum_j exp(s_j - m) * decode(V[j][c])        (v_scale not applied),
- * an empty row is (m = -inf, l = 0) and its acc is not read.
+ * an empty row is (m = -inf, l = 0) and its acc is ignored (it may hold anything).
  * Row i of a sequence holds the partial over the positions of chunks i .. i + r - 1, r >= 1, and
  * rows i + 1 .. i + r - 1 are empty: a workgroup that is given several consecutive chunks of one
  * sequence runs them as one online softmax and leaves one partial in the row of the first (which
