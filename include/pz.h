@@ -40,7 +40,8 @@
  *       PZ_APPEND_FORM=tile|token        quantise-and-append as 64-token tiles (large appends) or as one
  *                                        wave per (token, KV head) (decode-sized appends)
  *       PZ_APPEND_FUSED=1|0              pz_decode_attn_append writes the new token inside the attention
- *                                        launch (single-pass calls) or by a launch of its own first
+ *                                        launch (single-pass and small split-K calls) or by a launch of
+ *                                        its own first
  *
  * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
  * discuss paging):
@@ -176,10 +177,10 @@ pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
  * pz_kv_append_fp8 of one new token per sequence and pz_decode_attn in one call.  The paper's decode
  * step quantises the new token's K/V into the FP8 cache and then attends over the cache including
  * that token (Section 3, "KV Quantization"); this call does both, with the same arithmetic and the
- * same bytes as the two separate calls.  In single-pass calls the append runs inside the attention
- * launch (one launch less per decode step: at decode sizes the append is launch-bound); in split-K
- * calls, where that is slower, the call enqueues an append kernel of its own first -- it needs no
- * slot mapping either way.
+ * same bytes as the two separate calls.  In single-pass calls, and in split-K calls of a few
+ * sequences, the append runs inside the attention launch (one launch less per decode step: at decode
+ * sizes the append is launch-bound); in larger split-K calls, where that is slower, the call enqueues
+ * an append kernel of its own first -- it needs no slot mapping either way.
  *
  *   k_new, v_new : bf16 [batch][n_kv_heads][head_dim]; row b is written to the slot of position
  *                  L_b - 1 of sequence b, i.e. block_table[b][(L_b-1)/page_size] * page_size +

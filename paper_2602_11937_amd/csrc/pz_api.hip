@@ -185,12 +185,14 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     p.k = static_cast<uint8_t *>(cache->k);
     p.v = static_cast<uint8_t *>(cache->v);
     // The append runs inside the attention launch for single-pass calls (short windows: batch 256, window 128
-    // takes 15 us that way against 18 us).  In a split-K call the wave that attends the newest position
-    // is one of equally long, bandwidth-bound shares, and what it does besides (a dependent block-table
-    // read, 64 scattered V bytes) lengthens the whole launch by more than a launch of its own costs
-    // (batch 16, ragged: + 9 us; batch 256, window 8192: + 28 us), so there the token is appended by a
-    // launch of its own first: same bytes, same results.
-    bool in_kernel = fused_append && split_tokens == 0;
+    // takes 15 us that way against 18 us) and for split-K calls of a few sequences (up to 32 (sequence, KV
+    // head) pairs: batch 1 to 4 at 128K context each gain 2 us of 30 to 90).  In a larger split-K call the
+    // wave that attends the newest position is one of equally long, bandwidth-bound shares, and what it
+    // does besides (a dependent block-table read, 64 scattered V bytes) lengthens the whole launch by
+    // more than a launch of its own costs (batch 8 x 128K: + 5 us; batch 16, ragged: + 1 to 9 us; batch
+    // 256, window 8192: + 28 us), so there the token is appended by a launch of its own first: same
+    // bytes, same results.
+    bool in_kernel = fused_append && (split_tokens == 0 || (int64_t)batch * cache->n_kv_heads <= 32);
     if (fused_append && getenv("PZ_APPEND_FUSED") != nullptr) in_kernel = !env_is_zero("PZ_APPEND_FUSED");
     if (cache->n_kv_heads > 65535) in_kernel = fused_append;      // the append launch has one grid row per KV head
     p.k_new = in_kernel ? static_cast<const uint16_t *>(k_new) : nullptr;
