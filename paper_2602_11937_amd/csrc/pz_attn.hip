@@ -278,12 +278,12 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         }
         if (empty) return;                             // no chunk of the group holds a position: nothing is written
         emit_direct();
-        // burst the parked partials out: 16 lanes cover one 256-byte row, a wave-wide store covers
-        // 4 rows.  The stores are non-temporal: the partials are read once, by another kernel, and
-        // written through they do not wait in L2 for the write-back at the end of the kernel.
-        // Chunks of the group that lie beyond the context were never parked and are not written:
-        // the merge kernel bounds its reads by the sequence length.
-        __syncthreads();                               // lanes read what other lanes parked
+        // the group's partial goes out through LDS: 16 lanes cover one 256-byte row, a wave-wide
+        // store covers 4 rows.  The stores are non-temporal: a partial is read once, by another
+        // kernel, and written through it does not wait in L2 for the write-back at the end of the
+        // kernel.  Chunks of the group that lie beyond the context are not written at all: the merge
+        // kernel bounds its reads by the sequence length.
+        __syncthreads();                               // lanes read what other lanes put there
         const int n_rows = G;
         const int quad = lane & 15;
         for (int r0 = 0; r0 < n_rows; r0 += 16) {
