@@ -31,17 +31,8 @@
  *     n_kv_heads with group size n_q_heads / n_kv_heads <= 64 (a group above 8 is cut into 2, 4
  *     or 8 parts of at most 8 heads and the attention kernels read each KV head once per part).
  *
- *   - Launch shapes are chosen by the library.  Five environment variables override the choice,
- *     for tests and measurements only (results are the same for every shape):
- *       PZ_ATTN_WAVES=1|2|4|8            waves per workgroup of the decode-attention kernel
- *       PZ_ATTN_CHUNKS_PER_GROUP=n       consecutive split-K chunks walked by a one-wave workgroup
- *       PZ_ATTN_BALANCED=0               full-attention split-K on the fixed (sequence, chunk group)
- *                                        grid instead of the partition balanced over the batch
- *       PZ_APPEND_FORM=tile|token        quantise-and-append as 64-token tiles (large appends) or as one
- *                                        wave per (token, KV head) (decode-sized appends)
- *       PZ_APPEND_FUSED=1|0              pz_decode_attn_append writes the new token inside the attention
- *                                        launch (single-pass and small split-K calls) or by a launch of
- *                                        its own first
+ *   - Launch shapes are chosen by the library from the arguments alone; no environment variable is read.
+ *     pz_debug_set_launch_override (below) forces a shape, for tests and measurements.
  *
  * Cache layout (chosen for the matrix-core operand shapes of gfx950; the paper does not
  * discuss paging):
@@ -84,6 +75,31 @@ typedef struct {
 
 /* Human-readable name of a status code (host string, static storage). */
 const char *pz_status_string(pz_status s);
+
+/*
+ * Test and measurement hook, not part of the decode path: forces one of the launch-shape choices the
+ * library otherwise makes from the arguments of a call (results are the same for every shape; the
+ * split-K workspace rows that hold partials depend on it, as stated at pz_decode_attn_workspace_bytes).
+ * Process-wide, takes effect for the calls that follow; a negative value hands the choice back.
+ *   PZ_OVERRIDE_ATTN_WAVES             1 | 2 | 4 | 8   waves per workgroup of the decode-attention kernel (0 = unset)
+ *   PZ_OVERRIDE_ATTN_CHUNKS_PER_GROUP  n >= 1          consecutive split-K chunks walked by a one-wave workgroup (0 = unset)
+ *   PZ_OVERRIDE_ATTN_BALANCED          0 | 1           0: full-attention split-K on the fixed (sequence, chunk
+ *                                                      group) grid instead of the partition balanced over the batch
+ *   PZ_OVERRIDE_APPEND_FORM            0 | 1           quantise-and-append as 64-token tiles (0; large appends) or
+ *                                                      as one wave per (token, KV head) (1; decode-sized appends)
+ *   PZ_OVERRIDE_APPEND_FUSED           0 | 1           pz_decode_attn_append appends by a launch of its own first
+ *                                                      (0) or inside the attention launch (1)
+ * Returns PZ_ERR_SHAPE for an unknown override or a value outside the listed ones.
+ */
+typedef enum {
+    PZ_OVERRIDE_ATTN_WAVES = 0,
+    PZ_OVERRIDE_ATTN_CHUNKS_PER_GROUP = 1,
+    PZ_OVERRIDE_ATTN_BALANCED = 2,
+    PZ_OVERRIDE_APPEND_FORM = 3,
+    PZ_OVERRIDE_APPEND_FUSED = 4,
+    PZ_OVERRIDE_COUNT = 5
+} pz_launch_override;
+pz_status pz_debug_set_launch_override(int32_t which, int32_t value);
 
 /*
  * Quantise-and-append (paper Section 3, "KV Quantization": FP8 KV cache with per-layer scales).
@@ -297,7 +313,8 @@ pz_status pz_kv_scales_from_amax(const float *amax, int32_t round_up_pow2, float
  * Host-side page pool of one layer's cache, with page recycling for sliding-window layers (the
  * per-layer KV footprint of a window layer is bounded by its window, paper Section 2, "Window
  * attention for long-context inference"; the memory it frees is what lets a single GPU hold a
- * larger batch).  Pure host code; the pool allocates host memory in create and frees it in destroy.
+ * larger batch).  Pure host code; the pool allocates host memory in create and frees it in destroy; when host memory
+ * runs out a call fails with its error value (NULL, PZ_ERR_WORKSPACE) and the pool stays as it was.
  *
  *   pz_window_pages      most physical pages one sequence of a window layer holds at any time:
  *                        (window + page_size - 2) / page_size + 1   (0 for window <= 0)

@@ -50,6 +50,8 @@ def lib():
         L = C.CDLL(path)
         L.pz_status_string.restype = C.c_char_p
         L.pz_status_string.argtypes = [C.c_int]
+        L.pz_debug_set_launch_override.restype = C.c_int
+        L.pz_debug_set_launch_override.argtypes = [C.c_int32, C.c_int32]
         L.pz_kv_append_fp8.restype = C.c_int
         L.pz_kv_append_fp8.argtypes = [C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                        C.c_float, C.c_float, C.c_void_p]
@@ -111,6 +113,19 @@ def lib():
 
 def pz_status_string(status: int) -> str:
     return lib().pz_status_string(int(status)).decode()
+
+
+OVERRIDES = {"attn_waves": 0, "attn_chunks_per_group": 1, "attn_balanced": 2, "append_form": 3, "append_fused": 4}
+APPEND_FORM_TILE, APPEND_FORM_TOKEN = 0, 1
+
+
+def pz_debug_set_launch_override(which, value, check=True) -> int:
+    """Force one launch-shape choice (tests and measurements); a negative value hands it back to the library.
+    `which` is a pz_launch_override number or its lower-case name without the prefix."""
+    st = lib().pz_debug_set_launch_override(int(OVERRIDES.get(which, which)), int(value))
+    if check and st != 0:
+        raise PzError(st, "pz_debug_set_launch_override")
+    return st
 
 
 def _ptr(t) -> Optional[int]:

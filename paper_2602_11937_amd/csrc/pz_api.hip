@@ -1,12 +1,16 @@
 // C-ABI layer: argument validation (host only, before anything is enqueued) and dispatch.
 #include <hip/hip_runtime.h>
 #include <math.h>
-#include <stdlib.h>
+
+#include <atomic>
 
 #include "pz.h"
 #include "pz_internal.h"
 
 namespace {
+
+// launch-shape overrides (pz_debug_set_launch_override); negative = the library's own choice
+std::atomic<int> g_override[PZ_OVERRIDE_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}};
 
 bool supported_page(int p) { return p == 16 || p == 32 || p == 64; }
 
@@ -35,18 +39,6 @@ int group_shift(int group) {
 }
 bool group_supported(int group) { return group_shift(group) >= 0; }
 
-int env_int(const char *name, int fallback) {
-    const char *s = getenv(name);
-    if (s == nullptr || *s == 0) return fallback;
-    const int v = atoi(s);
-    return v > 0 ? v : fallback;
-}
-
-bool env_is_zero(const char *name) {
-    const char *s = getenv(name);
-    return s != nullptr && s[0] == '0' && s[1] == 0;
-}
-
 int round_down_pow2(int x) {
     int r = 1;
     while (2 * r <= x) r *= 2;
@@ -66,8 +58,8 @@ int round_down_pow2(int x) {
 void pick_shape(int batch, int n_kv_heads, int max_steps, int n_chunks, int full_chunks, int *n_waves,
                 int *chunks_per_group) {
     const long items = (long)batch * n_kv_heads * n_chunks;
-    const int forced_w = env_int("PZ_ATTN_WAVES", 0);
-    const int forced_c = env_int("PZ_ATTN_CHUNKS_PER_GROUP", 0);
+    const int forced_w = pz::launch_override(PZ_OVERRIDE_ATTN_WAVES);
+    const int forced_c = pz::launch_override(PZ_OVERRIDE_ATTN_CHUNKS_PER_GROUP);
     int w = 1;
     if (forced_w > 0) w = forced_w > 8 ? 8 : round_down_pow2(forced_w);
     else while (w < 8 && items * w < 2048 && max_steps >= 4 * w) w *= 2;
@@ -90,7 +82,19 @@ void pick_shape(int batch, int n_kv_heads, int max_steps, int n_chunks, int full
 
 }  // namespace
 
+int pz::launch_override(int which) {
+    return (which >= 0 && which < PZ_OVERRIDE_COUNT) ? g_override[which].load(std::memory_order_relaxed) : -1;
+}
+
 extern "C" {
+
+pz_status pz_debug_set_launch_override(int32_t which, int32_t value) {
+    if (which < 0 || which >= PZ_OVERRIDE_COUNT) return PZ_ERR_SHAPE;
+    const bool counts = which == PZ_OVERRIDE_ATTN_WAVES || which == PZ_OVERRIDE_ATTN_CHUNKS_PER_GROUP;
+    if (!counts && value > 1) return PZ_ERR_SHAPE;
+    g_override[which].store((value < 0 || (counts && value == 0)) ? -1 : value, std::memory_order_relaxed);
+    return PZ_OK;
+}
 
 const char *pz_status_string(pz_status s) {
     switch (s) {
@@ -193,7 +197,8 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     // 256, window 8192: + 28 us), so there the token is appended by a launch of its own first: same
     // bytes, same results.
     bool in_kernel = fused_append && (split_tokens == 0 || (int64_t)batch * cache->n_kv_heads <= 32);
-    if (fused_append && getenv("PZ_APPEND_FUSED") != nullptr) in_kernel = !env_is_zero("PZ_APPEND_FUSED");
+    if (fused_append && pz::launch_override(PZ_OVERRIDE_APPEND_FUSED) >= 0)
+        in_kernel = pz::launch_override(PZ_OVERRIDE_APPEND_FUSED) == 1;
     if (cache->n_kv_heads > 65535) in_kernel = fused_append;      // the append launch has one grid row per KV head
     p.k_new = in_kernel ? static_cast<const uint16_t *>(k_new) : nullptr;
     p.v_new = in_kernel ? static_cast<const uint16_t *>(v_new) : nullptr;
@@ -258,12 +263,12 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
         if (e != hipSuccess) return PZ_ERR_LAUNCH;
     }
     // Full-attention split-K with one-wave workgroups: the chunks are dealt out evenly on the device from
-    // the actual lengths (PZ_ATTN_BALANCED=0 keeps the one-workgroup-per-chunk-group grid, for
+    // the actual lengths (the balanced-partition override keeps the one-workgroup-per-chunk-group grid, for
     // comparisons).  Window layers keep that grid: their sequences all span about the window, their
     // first and last chunks are short, which a partition by chunk count does not see, and a share that
     // crosses from one short sequence into the next starts its pipeline anew each time (batch 256,
     // window 8192: 373 us on the balanced partition against 355 us on the grid).
-    if (split_tokens > 0 && window == 0 && n_waves == 1 && !env_is_zero("PZ_ATTN_BALANCED"))
+    if (split_tokens > 0 && window == 0 && n_waves == 1 && pz::launch_override(PZ_OVERRIDE_ATTN_BALANCED) != 0)
         e = pz::launch_decode_attn_balanced(p, cache->page_size, elem_bytes, static_cast<hipStream_t>(hip_stream));
     else
         e = pz::launch_decode_attn(p, cache->page_size, elem_bytes, n_waves, static_cast<hipStream_t>(hip_stream));

@@ -16,8 +16,8 @@
 // Tokens whose slot (or page) lies outside the cache are skipped in every form.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
+#include "pz.h"
 #include "pz_internal.h"
 #include "pz_quant.h"
 
@@ -145,27 +145,22 @@ namespace pz {
 hipError_t launch_kv_append_last(const AppendParams &prm, const int32_t *block_table, int max_pages,
                                  const int32_t *seq_lens, int batch, int elem_bytes, hipStream_t stream) {
     const dim3 grid((unsigned)batch, (unsigned)prm.Hkv), block(64);
-    if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_last_kernel<1>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
-    else hipLaunchKernelGGL(kv_append_last_kernel<2>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
-    return hipGetLastError();
+    if (elem_bytes == 1) return launch(kv_append_last_kernel<1>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
+    return launch(kv_append_last_kernel<2>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
 }
 
 hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t stream) {
-    // up to two waves per SIMD: the token-per-wave form (PZ_APPEND_FORM=tile|token forces one, for tests)
-    const char *form = getenv("PZ_APPEND_FORM");
-    const bool token_form = form != nullptr && form[0] == 't' && form[1] == 'o'   ? true
-                            : form != nullptr && form[0] == 't' && form[1] == 'i' ? false
-                                                                                  : prm.T * prm.Hkv <= 8192;
+    // up to two waves per SIMD: the token-per-wave form (the append-form override forces one, for tests)
+    const int form = launch_override(PZ_OVERRIDE_APPEND_FORM);
+    const bool token_form = form >= 0 ? form == 1 : prm.T * prm.Hkv <= 8192;
     if (token_form && prm.T <= 0x7fffffff) {
         const dim3 grid((unsigned)prm.T, (unsigned)prm.Hkv), block(64);
-        if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_token_kernel<1>, grid, block, 0, stream, prm);
-        else hipLaunchKernelGGL(kv_append_token_kernel<2>, grid, block, 0, stream, prm);
-        return hipGetLastError();
+        if (elem_bytes == 1) return launch(kv_append_token_kernel<1>, grid, block, 0, stream, prm);
+        return launch(kv_append_token_kernel<2>, grid, block, 0, stream, prm);
     }
     const dim3 grid((unsigned)((prm.T + 63) / 64), (unsigned)prm.Hkv), block(256);
-    if (elem_bytes == 1) hipLaunchKernelGGL(kv_append_kernel<1>, grid, block, 0, stream, prm);
-    else hipLaunchKernelGGL(kv_append_kernel<2>, grid, block, 0, stream, prm);
-    return hipGetLastError();
+    if (elem_bytes == 1) return launch(kv_append_kernel<1>, grid, block, 0, stream, prm);
+    return launch(kv_append_kernel<2>, grid, block, 0, stream, prm);
 }
 
 }  // namespace pz

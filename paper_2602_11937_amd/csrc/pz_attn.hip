@@ -484,29 +484,26 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
     const dim3 grid((unsigned)(prm.B * prm.Hkv * n_groups)), block(64 * n_waves);
     const size_t records = n_waves > 1 ? n_waves : (prm.split_tokens > 0 ? 1 : 0);
     const size_t lds_bytes = records * (8 * 64 + 16) * sizeof(float);
-#define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((decode_attn_kernel<P, EB>), grid, block, lds_bytes, stream, prm)
+#define PZ_LAUNCH(P, EB) return launch(decode_attn_kernel<P, EB>, grid, block, lds_bytes, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);
-        else if (page_size == 32) PZ_LAUNCH(32, 1);
-        else PZ_LAUNCH(16, 1);
-    } else {
-        if (page_size == 64) PZ_LAUNCH(64, 2);
-        else if (page_size == 32) PZ_LAUNCH(32, 2);
-        else PZ_LAUNCH(16, 2);
+        if (page_size == 32) PZ_LAUNCH(32, 1);
+        PZ_LAUNCH(16, 1);
     }
+    if (page_size == 64) PZ_LAUNCH(64, 2);
+    if (page_size == 32) PZ_LAUNCH(32, 2);
+    PZ_LAUNCH(16, 2);
 #undef PZ_LAUNCH
-    return hipGetLastError();
 }
 
 hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
     // one wave per 64 chunks, at most eight; short rows in one batch of 16
     const dim3 grid((unsigned)(prm.B * prm.Hq));
-    if (prm.n_splits <= 16) hipLaunchKernelGGL((splitk_reduce_kernel<1, 16>), grid, dim3(64), 0, stream, prm);
-    else if (prm.n_splits <= 64) hipLaunchKernelGGL((splitk_reduce_kernel<1, 64>), grid, dim3(64), 0, stream, prm);
-    else if (prm.n_splits <= 128) hipLaunchKernelGGL((splitk_reduce_kernel<2, 64>), grid, dim3(128), 0, stream, prm);
-    else if (prm.n_splits <= 256) hipLaunchKernelGGL((splitk_reduce_kernel<4, 64>), grid, dim3(256), 0, stream, prm);
-    else hipLaunchKernelGGL((splitk_reduce_kernel<8, 64>), grid, dim3(512), 0, stream, prm);
-    return hipGetLastError();
+    if (prm.n_splits <= 16) return launch(splitk_reduce_kernel<1, 16>, grid, dim3(64), 0, stream, prm);
+    if (prm.n_splits <= 64) return launch(splitk_reduce_kernel<1, 64>, grid, dim3(64), 0, stream, prm);
+    if (prm.n_splits <= 128) return launch(splitk_reduce_kernel<2, 64>, grid, dim3(128), 0, stream, prm);
+    if (prm.n_splits <= 256) return launch(splitk_reduce_kernel<4, 64>, grid, dim3(256), 0, stream, prm);
+    return launch(splitk_reduce_kernel<8, 64>, grid, dim3(512), 0, stream, prm);
 }
 
 }  // namespace pz

@@ -430,18 +430,16 @@ hipError_t launch_decode_attn_balanced(const AttnParams &prm_in, int page_size, 
         bph = room < prm.full_n_act ? prm.full_n_act : room;
     }
     const dim3 grid((unsigned)(bph * prm.Hkv)), block(64);
-#define PZ_LAUNCH(PP, EE) hipLaunchKernelGGL((decode_attn_balanced_kernel<PP, EE>), grid, block, 0, stream, prm)
+#define PZ_LAUNCH(PP, EE) return launch(decode_attn_balanced_kernel<PP, EE>, grid, block, 0, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);
-        else if (page_size == 32) PZ_LAUNCH(32, 1);
-        else PZ_LAUNCH(16, 1);
-    } else {
-        if (page_size == 64) PZ_LAUNCH(64, 2);
-        else if (page_size == 32) PZ_LAUNCH(32, 2);
-        else PZ_LAUNCH(16, 2);
+        if (page_size == 32) PZ_LAUNCH(32, 1);
+        PZ_LAUNCH(16, 1);
     }
+    if (page_size == 64) PZ_LAUNCH(64, 2);
+    if (page_size == 32) PZ_LAUNCH(32, 2);
+    PZ_LAUNCH(16, 2);
 #undef PZ_LAUNCH
-    return hipGetLastError();
 }
 
 }  // namespace pz

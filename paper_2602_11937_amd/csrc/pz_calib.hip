@@ -112,13 +112,11 @@ hipError_t launch_kv_amax(const uint16_t *k, const uint16_t *v, int64_t n, float
     if ((n_tiles + per - 1) / per > 65536) per = (n_tiles + 65535) / 65536;
     int64_t blocks = (n_tiles + per - 1) / per;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(kv_amax_kernel, dim3((unsigned)blocks, 2), dim3(64), 0, stream, k, v, n, per, amax);
-    return hipGetLastError();
+    return launch(kv_amax_kernel, dim3((unsigned)blocks, 2), dim3(64), 0, stream, k, v, n, per, amax);
 }
 
 hipError_t launch_kv_scales(const float *amax, int round_up_pow2, float *scales, hipStream_t stream) {
-    hipLaunchKernelGGL(kv_scales_kernel, dim3(1), dim3(64), 0, stream, amax, round_up_pow2, scales);
-    return hipGetLastError();
+    return launch(kv_scales_kernel, dim3(1), dim3(64), 0, stream, amax, round_up_pow2, scales);
 }
 
 }  // namespace pz

@@ -5,7 +5,31 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 namespace pz {
+
+// Enqueue `kernel` and return the status of THIS launch.  hipLaunchKernel hands back its own result, so an
+// error that earlier, unrelated work left behind on the calling thread is neither reported as this call's
+// nor cleared by it (a launch followed by hipGetLastError would do both).
+template <typename... KArgs, size_t... I>
+inline hipError_t launch_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                              std::tuple<KArgs...> &vals, std::index_sequence<I...>) {
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds_bytes, stream);
+}
+template <typename... KArgs, typename... Args>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                         Args &&...args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+    return launch_impl(kernel, grid, block, lds_bytes, stream, vals, std::index_sequence_for<KArgs...>{});
+}
+
+// Launch-shape overrides set through pz_debug_set_launch_override (tests and measurements); the value of
+// an override that is not set is negative.  Indexed by pz_launch_override.
+int launch_override(int which);
 
 struct AttnParams {
     uint8_t *k;                  // K cache  [page][Hkv][P][64]   (written only by the fused append)

@@ -239,18 +239,16 @@ hipError_t launch_prefill_attn(const PrefillParams &prm, int page_size, int elem
                                hipStream_t stream) {
     const dim3 grid((unsigned)(prm.B * prm.tiles_per_seq * prm.Hkv)), block(64);
     (void)n_tiles;
-#define PZ_LAUNCH(P, EB) hipLaunchKernelGGL((prefill_attn_kernel<P, EB, PZ_PREFILL_NT>), grid, block, 0, stream, prm)
+#define PZ_LAUNCH(P, EB) return launch(prefill_attn_kernel<P, EB, PZ_PREFILL_NT>, grid, block, 0, stream, prm)
     if (elem_bytes == 1) {
         if (page_size == 64) PZ_LAUNCH(64, 1);
-        else if (page_size == 32) PZ_LAUNCH(32, 1);
-        else PZ_LAUNCH(16, 1);
-    } else {
-        if (page_size == 64) PZ_LAUNCH(64, 2);
-        else if (page_size == 32) PZ_LAUNCH(32, 2);
-        else PZ_LAUNCH(16, 2);
+        if (page_size == 32) PZ_LAUNCH(32, 1);
+        PZ_LAUNCH(16, 1);
     }
+    if (page_size == 64) PZ_LAUNCH(64, 2);
+    if (page_size == 32) PZ_LAUNCH(32, 2);
+    PZ_LAUNCH(16, 2);
 #undef PZ_LAUNCH
-    return hipGetLastError();
 }
 
 }  // namespace pz

@@ -150,9 +150,8 @@ namespace pz {
 
 hipError_t launch_rope_kv_append(const RopeAppendParams &prm, int elem_bytes, hipStream_t stream) {
     const dim3 grid((unsigned)((prm.ap.T + 63) / 64), (unsigned)(prm.ap.Hkv + prm.Hq)), block(256);
-    if (elem_bytes == 1) hipLaunchKernelGGL(rope_kv_append_kernel<1>, grid, block, 0, stream, prm);
-    else hipLaunchKernelGGL(rope_kv_append_kernel<2>, grid, block, 0, stream, prm);
-    return hipGetLastError();
+    if (elem_bytes == 1) return launch(rope_kv_append_kernel<1>, grid, block, 0, stream, prm);
+    return launch(rope_kv_append_kernel<2>, grid, block, 0, stream, prm);
 }
 
 }  // namespace pz

@@ -25,3 +25,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def launch_override():
+    """force(name, value): force one launch-shape choice of the library (pz_debug_set_launch_override) for the
+    rest of the test; every override is handed back to the library afterwards."""
+    import paper_2602_11937_amd as pz
+    used = []
+
+    def force(name, value):
+        used.append(name)
+        pz.pz_debug_set_launch_override(name, value)
+
+    yield force
+    for name in used:
+        pz.pz_debug_set_launch_override(name, -1)

@@ -133,7 +133,21 @@ def check_workspace_rows(acc, ml, oacc, oml, tol):
     """The split-K workspace of the GPU path ([B][Hq][S][d] and [B][Hq][S][2]) against the oracle's
     per-chunk partials.  A row is unwritten (chunk without an attended position), empty (m = -inf,
     l = 0: its chunk was merged into an earlier row) or holds the partial of the run of chunks from
-    itself to the next row that is not empty.  Returns the number of rows that hold a partial."""
+    itself to the next row that is not empty.  Returns the number of rows that hold a partial.
+
+    Two quantities of a partial do not depend on its reference maximum: acc / l (bar: `tol`, the
+    output tolerance) and the log-sum-exp m + ln l.  The bound on the latter, 1e-4 in natural-log
+    units, follows from the kernel's arithmetic against an exact evaluation (the oracle side is
+    accumulated in fp64 and stored as fp32: 2e-6):
+      * each weight p_j enters l as two truncated bf16 terms, 16 significant bits: a one-sided
+        relative deficit below 2^-15 per term, so ln l is low by at most 3.1e-5;
+      * a logit is an fp32 sum of 64 exact products, scaled by the fp32 constant
+        sm_scale * k_scale * log2(e) (two roundings) inside one fused multiply-add: at most
+        (64 + 3) * 2^-24 of sum_c |q_c k_c| * sm_scale * k_scale, which is 4e-6 per unit of that sum;
+        the test cases keep the sum below 10 for the positions that carry weight: 4e-5;
+      * the hardware exp2 (1 ulp), the rescaling of l by exp2(m_old - m_new) once per 64 positions
+        (a rounding each, at most 128 of them in these cases) and m * ln 2 in fp32: 1.5e-5 together.
+    The three add up to 8.6e-5 in the worst case, all signs aligned."""
     B, Hq, S, _ = acc.shape
     n_partials = 0
     worst_avg, worst_lse = 0.0, 0.0
@@ -156,6 +170,6 @@ def check_workspace_rows(acc, ml, oacc, oml, tol):
             rms = float(np.sqrt(np.mean(avg_o ** 2)))
             worst_avg = max(worst_avg, float(np.max(np.abs(avg_g - avg_o))) / (rms if rms > 0 else 1.0))
             n_partials += len(starts)
-    assert worst_lse < 2e-4, worst_lse
+    assert worst_lse < 1e-4, worst_lse
     assert worst_avg <= tol, worst_avg
     return n_partials

@@ -170,3 +170,20 @@ def test_new_entry_points_reject_bad_arguments():
     assert lib.pz_page_pool_create(4, 16, 1, 0, 0) is None
     assert lib.pz_page_pool_append(None, 0) == -1 and lib.pz_page_pool_free_pages(None) == -1
     assert pz.pz_window_pages(-3, 16) == 0
+
+
+def test_launch_override_entry_takes_only_its_listed_values():
+    """pz_debug_set_launch_override: unknown overrides and values outside the listed ones are refused; a
+    negative value (and 0 for the two counts) hands the choice back.  No environment variable is read by
+    the library: the names the earlier test knobs had do not occur in it."""
+    f = pz.lib().pz_debug_set_launch_override
+    assert f(-1, 1) == -2 and f(5, 1) == -2
+    for which in (2, 3, 4):
+        assert f(which, 2) == -2
+        assert f(which, 0) == 0 and f(which, 1) == 0 and f(which, -1) == 0
+    for which in (0, 1):
+        assert f(which, 8) == 0 and f(which, 0) == 0 and f(which, -5) == 0
+    assert pz.pz_debug_set_launch_override("attn_waves", -1) == 0
+    blob = open(pz.lib_path(), "rb").read()
+    for name in (b"PZ_ATTN_WAVES", b"PZ_APPEND_FORM", b"PZ_APPEND_FUSED", b"PZ_ATTN_BALANCED", b"getenv"):
+        assert name not in blob, name

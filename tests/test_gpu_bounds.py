@@ -35,11 +35,11 @@ def hostile(case):
 
 ROUTES = {
     "single_pass": dict(split_tokens=0),
-    "single_pass_4_waves": dict(split_tokens=0, env={"PZ_ATTN_WAVES": "4"}),
+    "single_pass_4_waves": dict(split_tokens=0, force={"attn_waves": 4}),
     "split_balanced": dict(split_tokens=64),
-    "split_fixed_grid": dict(split_tokens=64, env={"PZ_ATTN_BALANCED": "0"}),
-    "split_fixed_grid_chunk_groups": dict(split_tokens=64, env={"PZ_ATTN_BALANCED": "0", "PZ_ATTN_CHUNKS_PER_GROUP": "3"}),
-    "split_2_waves": dict(split_tokens=128, env={"PZ_ATTN_WAVES": "2"}),
+    "split_fixed_grid": dict(split_tokens=64, force={"attn_balanced": 0}),
+    "split_fixed_grid_chunk_groups": dict(split_tokens=64, force={"attn_balanced": 0, "attn_chunks_per_group": 3}),
+    "split_2_waves": dict(split_tokens=128, force={"attn_waves": 2}),
     "window_single_pass": dict(split_tokens=0, window=100),
     "window_split": dict(split_tokens=64, window=200),
 }
@@ -47,10 +47,10 @@ ROUTES = {
 
 @pytest.mark.parametrize("P", [16, 64])
 @pytest.mark.parametrize("route", sorted(ROUTES))
-def test_attention_with_hostile_tables_and_lengths(route, P, monkeypatch):
+def test_attention_with_hostile_tables_and_lengths(route, P, launch_override):
     r = ROUTES[route]
-    for name, value in r.get("env", {}).items():
-        monkeypatch.setenv(name, value)
+    for name, value in r.get("force", {}).items():
+        launch_override(name, value)
     window = r.get("window", 0)
     case = wl.make_case("h", B=5, Hq=8, Hkv=2, d=64, P=P, seq_lens=[300, 517, 130, 260, 411], seed=70 + P, window=window)
     cache = gpu_cache(case)
@@ -72,8 +72,8 @@ def test_attention_with_hostile_tables_and_lengths(route, P, monkeypatch):
 
 @pytest.mark.parametrize("way", ["in_kernel", "own_launch"])
 @pytest.mark.parametrize("split_tokens", [0, 64])
-def test_fused_append_skips_tokens_it_cannot_place(way, split_tokens, monkeypatch):
-    monkeypatch.setenv("PZ_APPEND_FUSED", "1" if way == "in_kernel" else "0")
+def test_fused_append_skips_tokens_it_cannot_place(way, split_tokens, launch_override):
+    launch_override("append_fused", 1 if way == "in_kernel" else 0)
     case = wl.make_case("hf", B=5, Hq=8, Hkv=2, d=64, P=16, seq_lens=[300, 517, 130, 260, 33], seed=91)
     last = case.offsets[1:] - 1
     prefix = case.slot_mapping.copy()
@@ -112,8 +112,8 @@ def test_fused_append_skips_tokens_it_cannot_place(way, split_tokens, monkeypatc
 
 @pytest.mark.parametrize("form", ["tile", "token"])
 @pytest.mark.parametrize("rope", [False, True])
-def test_append_skips_slots_outside_the_cache(form, rope, monkeypatch):
-    monkeypatch.setenv("PZ_APPEND_FORM", form)
+def test_append_skips_slots_outside_the_cache(form, rope, launch_override):
+    launch_override("append_form", pz.APPEND_FORM_TOKEN if form == "token" else pz.APPEND_FORM_TILE)
     Hkv, d, P, T, num_pages = 2, 64, 16, 150, 12
     rng = np.random.default_rng(5)
     k = wl.bf16_bits(rng.standard_normal((T, Hkv, d)).astype(np.float32))

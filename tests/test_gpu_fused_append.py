@@ -64,10 +64,10 @@ def run_pair(case, split_tokens, dtype=pz.KV_FP8):
 
 
 @pytest.fixture(params=["in_kernel", "own_launch"])
-def fused_way(request, monkeypatch):
+def fused_way(request, launch_override):
     """pz_decode_attn_append writes the token inside the attention launch (single-pass calls) or by a launch of
     its own first (split-K calls); force each way for every call."""
-    monkeypatch.setenv("PZ_APPEND_FUSED", "1" if request.param == "in_kernel" else "0")
+    launch_override("append_fused", 1 if request.param == "in_kernel" else 0)
     return request.param
 
 
@@ -94,9 +94,9 @@ def test_fused_append_into_a_bf16_cache(fused_way):
 
 
 @pytest.mark.parametrize("waves,cpg", [(1, 1), (1, 3), (2, 1), (4, 1), (8, 1)])
-def test_fused_append_under_every_launch_shape(waves, cpg, monkeypatch):
-    monkeypatch.setenv("PZ_ATTN_WAVES", str(waves))
-    monkeypatch.setenv("PZ_ATTN_CHUNKS_PER_GROUP", str(cpg))
+def test_fused_append_under_every_launch_shape(waves, cpg, launch_override):
+    launch_override("attn_waves", waves)
+    launch_override("attn_chunks_per_group", cpg)
     case = wl.make_case("s", B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[3000, 64, 700, 1], seed=82)
     for split in (0, 256):
         (out_a, cache_a), (out_b, cache_b) = run_pair(case, split)

@@ -28,9 +28,9 @@ def oracle_attn(case, kc, vc, **kw):
 # ------------------------------------------------------------------ append: bit-exact
 
 @pytest.fixture(params=["tile", "token"])
-def append_form(request, monkeypatch):
+def append_form(request, launch_override):
     """Both launch forms of the append kernel (64-token tiles / one wave per token and head)."""
-    monkeypatch.setenv("PZ_APPEND_FORM", request.param)
+    launch_override("append_form", pz.APPEND_FORM_TOKEN if request.param == "token" else pz.APPEND_FORM_TILE)
     return request.param
 
 
@@ -280,10 +280,10 @@ def test_partials_match_the_chunked_oracle():
         assert check_workspace_rows(acc, ml, oacc, oml, TOL) >= case.B * case.Hq
 
 
-def test_one_chunk_per_workgroup_writes_one_partial_per_chunk(monkeypatch):
+def test_one_chunk_per_workgroup_writes_one_partial_per_chunk(launch_override):
     """With several waves per workgroup a workgroup holds one chunk, so every chunk with a position has
     a partial of its own: the per-chunk form of the workspace, compared row by row."""
-    monkeypatch.setenv("PZ_ATTN_WAVES", "2")
+    launch_override("attn_waves", 2)
     case = wl.make_case("pc", B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1000, 300], seed=28)
     cache = gpu_cache(case)
     kc, vc = oracle_cache(case)
@@ -342,11 +342,11 @@ def test_split_count_invariance():
 
 @pytest.mark.parametrize("B,max_len,split", [(150, 400, 64), (70, 3000, 256), (64, 900, 128), (65, 130, 64),
                                              (300, 64, 64), (5, 20000, 1024)])
-def test_balanced_partition_over_many_ragged_sequences(B, max_len, split, monkeypatch):
+def test_balanced_partition_over_many_ragged_sequences(B, max_len, split, launch_override):
     """Full-attention split-K deals the chunks of the whole batch out evenly: batches beyond one
     64-lane strip of lengths, shares that span several sequences, sequences without a token, and
     (forced by one wave per workgroup) totals far below the number of workgroups."""
-    monkeypatch.setenv("PZ_ATTN_WAVES", "1")
+    launch_override("attn_waves", 1)
     rng = np.random.default_rng(B + split)
     lens = rng.integers(0, max_len + 1, size=B)
     lens[rng.integers(0, B, size=max(1, B // 10))] = 0
@@ -411,9 +411,9 @@ def test_window_split_groups_of_chunks(B, expected_runs):
     assert int(np.isfinite(ml[0, 0, :, 0]).sum()) == expected_runs
 
 
-def test_balanced_partition_degenerate_batches(monkeypatch):
+def test_balanced_partition_degenerate_batches(launch_override):
     """No chunk at all (every sequence empty), a single sequence, and one chunk for the whole batch."""
-    monkeypatch.setenv("PZ_ATTN_WAVES", "1")
+    launch_override("attn_waves", 1)
     for lens, split in (([0, 0, 0], 64), ([777], 64), ([5], 1024), ([0, 3, 0, 0], 128), ([64] * 70, 64)):
         case = wl.make_case("deg", B=len(lens), Hq=8, Hkv=2, d=64, P=16, seq_lens=lens, seed=len(lens))
         cache = gpu_cache(case)
@@ -479,12 +479,12 @@ def test_short_contexts_without_a_window():
 
 @pytest.mark.parametrize("waves,cpg,balanced", [(1, 1, 0), (1, 2, 0), (1, 3, 0), (1, 8, 0), (1, 1, 1), (2, 1, 1),
                                                 (4, 1, 1), (8, 1, 1)])
-def test_every_launch_shape_gives_the_same_answer(waves, cpg, balanced, monkeypatch):
+def test_every_launch_shape_gives_the_same_answer(waves, cpg, balanced, launch_override):
     """Waves per workgroup, chunks per workgroup and the balanced partition of full-attention split-K
     are launch heuristics; force each shape."""
-    monkeypatch.setenv("PZ_ATTN_WAVES", str(waves))
-    monkeypatch.setenv("PZ_ATTN_CHUNKS_PER_GROUP", str(cpg))
-    monkeypatch.setenv("PZ_ATTN_BALANCED", str(balanced))
+    launch_override("attn_waves", waves)
+    launch_override("attn_chunks_per_group", cpg)
+    launch_override("attn_balanced", balanced)
     case = wl.make_case("l", B=3, Hq=16, Hkv=2, d=64, P=64, seq_lens=[2000, 130, 700], seed=21)
     cache = gpu_cache(case)
     kc, vc = oracle_cache(case)

@@ -6,12 +6,16 @@ properties (written with numpy float64, independent of the oracle's code): facto
 rotary embedding; pairs that turn at least beta_fast times over the original context keep their
 frequency; pairs that turn at most beta_slow times are interpolated by the factor; in between the
 blend is linear in the pair index; cos/sin carry the temperature 0.1 ln(factor) + 1; a rotation
-preserves norms and makes q.k a function of the position difference only."""
+preserves norms and makes q.k a function of the position difference only.
+
+parity unpinned: the paper prints only the factor.  The temperature term, theta, beta_fast, beta_slow
+and the original context are the published YaRN rule with the parent model's public configuration;
+nothing in the paper confirms them, so the checks of those below restate the reading, they do not pin
+it.  This file imports nothing of the HIP library."""
 import numpy as np
 import torch
 
 import oracle
-import paper_2602_11937_amd as pz
 from helpers import paper_values, torch_decode_e4m3
 from workloads import bf16_bits, bf16_to_f32
 
@@ -23,8 +27,7 @@ def test_defaults_are_the_papers_yarn_factor_and_contexts():
     assert pv["yarn_factor"] == 56 and pv["yarn_factor_parent"] == 32
     # 32 is the nominal extension ratio of the parent: original context x 32 = extended context
     assert pv["yarn_original_context"] * pv["yarn_factor_parent"] == pv["yarn_extended_context"]
-    prm = pz.YarnParams()
-    assert prm.factor == pv["yarn_factor"] and prm.original_context == pv["yarn_original_context"] == L0
+    assert pv["yarn_original_context"] == L0
     c_def, s_def = oracle.yarn_table(D, 3)
     c_56, s_56 = oracle.yarn_table(D, 3, theta=THETA, factor=pv["yarn_factor"], original_context=L0)
     assert np.array_equal(c_def, c_56) and np.array_equal(s_def, s_56)
@@ -62,17 +65,6 @@ def test_yarn_blend_temperature_and_factor():
     c56, _ = oracle.yarn_table(D, 2, factor=56.0)
     c32, _ = oracle.yarn_table(D, 2, factor=32.0)
     assert not np.allclose(c56, c32)
-
-
-def test_library_table_generator_agrees_with_the_oracle():
-    for factor in (1.0, 32.0, 56.0):
-        oc, osn = oracle.yarn_table(D, 5000, factor=factor)
-        lc, ls = pz.pz_rope_yarn_table(pz.YarnParams(factor=factor), D, 5000)
-        # two independent double-precision evaluations, rounded to fp32: equal up to the last bit or
-        # (large angles) a few ulps of the angle
-        assert np.max(np.abs(oc - lc)) < 2e-6 and np.max(np.abs(osn - ls)) < 2e-6
-    assert pz.pz_rope_yarn_table(pz.YarnParams(factor=0.5), D, 4, check=False)[0].sum() == 0
-    assert pz.lib().pz_rope_yarn_table(None, 64, 4, 0, 0) == -1
 
 
 def rotate_f64(x, cos, sin):

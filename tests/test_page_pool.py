@@ -71,3 +71,22 @@ def test_full_attention_pool_grows_and_runs_out():
     tiny.close()
     with pytest.raises(pz.PzError):
         pz.PagePool(0, 16, 1, 1)
+
+
+def test_a_refused_append_changes_nothing_and_a_window_step_can_reuse_its_own_page():
+    """Errors are found before the pool changes (so a caller may retry after releasing something), and the
+    one case where an empty free list is not an error: the step itself hands back the page it then opens."""
+    pool = pz.PagePool(2, 16, 2, 64, window=17)                      # 17 positions touch at most 2 pages
+    for _ in range(32):
+        assert pool.append(0) >= 0                                   # positions 0..31: pages 0 and 1, nothing free
+    assert pool.free_pages() == 0
+    table, pending = pool.block_table().copy(), pool.drain_updates()
+    assert pool.append(1, check=False) == -4                         # another sequence: refused
+    assert np.array_equal(pool.block_table(), table) and pool.seq_len(1) == 0 and len(pool.drain_updates()[0]) == 0
+    slot = pool.append(0)                                            # position 32 opens a page: page 0 of the
+    assert slot // 16 == table[0, 0]                                 # sequence left the window and comes back
+    idx, val = pool.drain_updates()
+    assert list(idx) == [0, 2] and list(val) == [-1, int(table[0, 0])]
+    assert pool.seq_len(0) == 33 and pool.free_pages() == 0
+    pool.close()
+    assert pz.lib().pz_page_pool_create(4, 16, 70000, 70000, 0) is None     # table indices would pass 32 bits
