@@ -34,12 +34,18 @@ def oracle_sequences(layer, seqs):
         assert np.array_equal(gk, kc[first:first + L - fp]) and np.array_equal(gv, vc[first:first + L - fp])
     sinks = lay.sinks.cpu().numpy()
     return [oracle.decode_attn(kc, vc, P, q, bt, lay.seq_lens[seqs], sinks, lay.sm_scale, lay.k_scale,
-                               lay.v_scale, layer.window, accum=a, nthreads=16) for a in ("f32", "f64")]
+                               lay.v_scale, layer.window, accum=a, nthreads=bench.host_cores()) for a in ("f32", "f64")]
 
 
-@pytest.mark.parametrize("name,seqs", [("cfg3", [0, 9]), ("cfg2", [3, 40, 63]), ("cfg4_w128", [0, 100, 255]),
-                                       ("cfg4_w8192", [0, 100, 255]), ("cfg5_w128", [0, 31]),
-                                       ("cfg5_w8192", [0, 17, 31]), ("cfg5_full", [5, 31])])
+# The whole batch where the oracle finishes it in seconds (cfg3, cfg2), else a run of consecutive sequences plus
+# the last one: shares of the balanced partition and chunk groups that cross from one sequence into the next are
+# then compared on both sides of the crossing.
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,seqs", [("cfg3", list(range(16))), ("cfg2", list(range(64))),
+                                       ("cfg4_w128", list(range(96, 128)) + [0, 255]),
+                                       ("cfg4_w8192", list(range(96, 112)) + [0, 255]),
+                                       ("cfg5_w128", list(range(32))), ("cfg5_w8192", list(range(8, 20)) + [0, 31]),
+                                       ("cfg5_full", list(range(4, 12)) + [31])])
 def test_bench_configuration_against_oracle_on_sampled_sequences(name, seqs):
     spec = bench.WORKLOADS[name]
     layer = bench.Layer(pz, wl, torch, spec, seed=spec["seed"], kv_dtype=pz.KV_FP8, keep_context=True)
@@ -53,8 +59,13 @@ def test_bench_configuration_against_oracle_on_sampled_sequences(name, seqs):
     got = out[seqs]
     want32, want64 = oracle_sequences(layer, seqs)
     e32, e64 = rel_err(got, want32), rel_err(got, want64)
-    print("%s: sampled sequences %s: err vs f32 oracle %.2e, vs f64 oracle %.2e" % (name, seqs, e32, e64))
-    assert e32 <= TOL and e64 <= TOL
+    print("%s: %d sampled sequences: err vs f32 oracle %.2e, vs f64 oracle %.2e" % (name, len(seqs), e32, e64))
+    # The bar is against the oracle in fp64.  Its fp32 variant adds every sequence's weights and weighted values
+    # one after the other in fp32: over L terms of one sign that loses up to L * 2^-24 of the sum (3.9e-3 at
+    # 65536 positions; measured 3.3e-3 on the worst of cfg3's sixteen sequences, where the fp64 variant and the
+    # GPU agree to 1e-4), so against it the bar is widened by exactly that much.
+    L_max = int(layer.lay.seq_lens.max()) if layer.window == 0 else min(int(layer.lay.seq_lens.max()), layer.window)
+    assert e64 <= TOL and e32 <= TOL + L_max * 2.0 ** -24
     layer.lay.k_ctx = layer.lay.v_ctx = None
     del layer
     torch.cuda.empty_cache()

@@ -25,8 +25,12 @@ E4M3_MAX = 448.0
 def bf16_bits(x: np.ndarray) -> np.ndarray:
     """fp32 -> bf16 bit patterns, round to nearest even (finite inputs)."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    r = ((u >> 16) & 1) + np.uint32(0x7FFF)
-    return ((u + r) >> 16).astype(np.uint16)
+    r = u >> 16                                        # one temporary, updated in place
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= 16
+    return r.astype(np.uint16)
 
 
 def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
@@ -107,8 +111,12 @@ def paged_tables(rng: np.random.Generator, seq_lens: np.ndarray, P: int, spare_p
 def make_case(name: str, *, B: int, Hq: int, Hkv: int, d: int, P: int, seq_lens, window: int = 0,
               seed: int = 0, sinks: bool = True, sm_scale: Optional[float] = None,
               split_tokens: int = 0, outlier_frac: float = 0.0, outlier_gain: float = 20.0,
-              pow2_scales: bool = False, unit_scales: bool = False) -> Case:
+              pow2_scales: bool = False, unit_scales: bool = False, k_gain: float = 1.0,
+              v_gain: float = 1.0) -> Case:
     """q, k, v ~ N(0,1) rounded to bf16; sinks ~ N(0,1) fp32; scales = amax/448 per tensor.
+
+    k_gain / v_gain multiply K / V before the rounding to bf16 (layers of a model differ in the magnitude
+    of their activations, hence in their calibrated scales).
 
     outlier_frac > 0 multiplies round(outlier_frac * Hkv * d) seeded (kv-head, channel) pairs of
     K by `outlier_gain` for every token before calibration (outlier channels)."""
@@ -119,6 +127,10 @@ def make_case(name: str, *, B: int, Hq: int, Hkv: int, d: int, P: int, seq_lens,
     q = rng.standard_normal((B, Hq, d), dtype=np.float32)
     k = rng.standard_normal((T, Hkv, d), dtype=np.float32)
     v = rng.standard_normal((T, Hkv, d), dtype=np.float32)
+    if k_gain != 1.0:
+        k *= np.float32(k_gain)
+    if v_gain != 1.0:
+        v *= np.float32(v_gain)
     extra = {}
     if outlier_frac > 0:
         n_out = int(round(outlier_frac * Hkv * d))
