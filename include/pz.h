@@ -230,6 +230,28 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
                                        void *out, int32_t out_dtype, void *hip_stream);
 
 /*
+ * pz_decode_attn + pz_decode_attn_splitk_reduce in one call that allocates nothing and takes no
+ * workspace: for callers that can neither call hipMalloc nor bring device memory beyond the inputs and the
+ * output -- code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  The
+ * split-K partials go to a device array that is part of the library (PZ_NOALLOC_WORKSPACE_BYTES, held on
+ * every GPU the library runs on from the load of its code until the process ends); its address on the
+ * current device is looked up at the first call with that device current (make that call outside a
+ * capture) and kept.  Arguments and results exactly as the two calls with a workspace of
+ * pz_decode_attn_workspace_bytes(batch, n_q_heads, 64, n_splits) bytes; `out` is written by this call.
+ *   PZ_ERR_WORKSPACE   the partials of the call would not fit the array (nothing is enqueued)
+ *   split_tokens == 0  single pass, no partials: the same as pz_decode_attn (n_splits ignored)
+ * seq_lens is required (the merge uses only the rows this call wrote; what the array keeps from earlier
+ * calls is never used, so nothing is cleared).  All calls on one GPU share the one array: calls that
+ * overlap on a GPU -- different streams, different host threads -- race; calls on one stream do not.
+ */
+#define PZ_NOALLOC_WORKSPACE_BYTES (32u << 20)
+pz_status pz_decode_attn_noalloc(const pz_cache *cache /* host */, const void *q, const int32_t *block_table,
+                                 int32_t max_pages_per_seq, const int32_t *seq_lens, int32_t batch,
+                                 int32_t n_q_heads, const float *sinks, float sm_scale, float k_scale,
+                                 float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits, void *out,
+                                 int32_t out_dtype, void *hip_stream);
+
+/*
  * Multi-token (prefill / chunked-prefill) attention over the paged cache: the input half of the
  * paper's fixed-length serving scenarios (Section 4, 4K/4K and 64K/64K input/output), with the
  * same per-layer window rule and the same FP8 cache as the decode call.

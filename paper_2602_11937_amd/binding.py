@@ -69,6 +69,10 @@ def lib():
                                             C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_float,
                                             C.c_float, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
                                             C.c_size_t, C.c_void_p, C.c_int32, C.c_void_p]
+        L.pz_decode_attn_noalloc.restype = C.c_int
+        L.pz_decode_attn_noalloc.argtypes = [C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
+                                             C.c_int32, C.c_int32, C.c_void_p, C.c_float, C.c_float, C.c_float,
+                                             C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
         L.pz_decode_attn_splitk_reduce.restype = C.c_int
         L.pz_decode_attn_splitk_reduce.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32,
                                                    C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
@@ -210,6 +214,21 @@ def pz_decode_attn(cache, q, block_table, max_pages_per_seq, seq_lens, batch, n_
                               _stream(stream))
     if check and st != 0:
         raise PzError(st, "pz_decode_attn")
+    return st
+
+
+NOALLOC_WORKSPACE_BYTES = 32 << 20
+
+
+def pz_decode_attn_noalloc(cache, q, block_table, max_pages_per_seq, seq_lens, batch, n_q_heads, sinks, sm_scale,
+                           k_scale, v_scale, window, split_tokens, n_splits, out, out_dtype=OUT_F32, stream=None,
+                           check=True) -> int:
+    st = lib().pz_decode_attn_noalloc(_cache_ref(cache), _ptr(q), _ptr(block_table), int(max_pages_per_seq),
+                                      _ptr(seq_lens), int(batch), int(n_q_heads), _ptr(sinks), float(sm_scale),
+                                      float(k_scale), float(v_scale), int(window), int(split_tokens), int(n_splits),
+                                      _ptr(out), int(out_dtype), _stream(stream))
+    if check and st != 0:
+        raise PzError(st, "pz_decode_attn_noalloc")
     return st
 
 

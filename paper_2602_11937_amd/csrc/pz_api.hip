@@ -333,6 +333,69 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
 }
 
+}  // extern "C"
+
+// ---- the entry point that allocates nothing -------------------------------------------------------------
+// Split-K workspace of pz_decode_attn_noalloc: a device array of the library itself, one copy per GPU,
+// held from the moment the code object is loaded on that GPU until the process ends.
+static __device__ __align__(256) unsigned char scratch[PZ_NOALLOC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+// address of `scratch` on each device, resolved at the first call with that device current (the array's
+// name is only a host-side handle: kernels are given this pointer)
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+pz_status scratch_of_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PZ_ERR_LAUNCH;
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return PZ_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);      // two threads resolve the same address
+    }
+    *out = ptr;
+    return PZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+pz_status pz_decode_attn_noalloc(const pz_cache *cache, const void *q, const int32_t *block_table,
+                                 int32_t max_pages_per_seq, const int32_t *seq_lens, int32_t batch,
+                                 int32_t n_q_heads, const float *sinks, float sm_scale, float k_scale,
+                                 float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits, void *out,
+                                 int32_t out_dtype, void *hip_stream) {
+    if (out == nullptr && batch > 0) return PZ_ERR_NULL;
+    if (split_tokens <= 0)                              // single pass: no scratch at all
+        return decode_attn_impl(cache, nullptr, nullptr, false, q, block_table, max_pages_per_seq, seq_lens, batch,
+                                n_q_heads, sinks, sm_scale, k_scale, v_scale, window, split_tokens, 0, nullptr, 0, out,
+                                out_dtype, hip_stream);
+    if (batch < 0 || n_q_heads <= 0 || n_splits <= 0) return PZ_ERR_SHAPE;
+    if (batch == 0) return PZ_OK;
+    if (cache == nullptr) return PZ_ERR_NULL;
+    // the partials of the call must fit the array: refused here, before anything is enqueued
+    if ((uint64_t)batch * (uint64_t)n_q_heads * (uint64_t)n_splits > PZ_NOALLOC_WORKSPACE_BYTES / ((64 + 2) * sizeof(float)))
+        return PZ_ERR_WORKSPACE;
+    const size_t need = pz_decode_attn_workspace_bytes(batch, n_q_heads, cache->head_dim, n_splits);
+    if (need == 0 || need > (size_t)PZ_NOALLOC_WORKSPACE_BYTES) return PZ_ERR_WORKSPACE;
+    void *ws = nullptr;
+    const pz_status ss = scratch_of_current_device(&ws);
+    if (ss != PZ_OK) return ss;
+    // Nothing of the array has to start at zero: the first pass writes every row that the merge uses (the
+    // rows of the chunks that hold attended positions of a sequence), the merge bounds itself by the same
+    // lengths, and what the array keeps from an earlier call in its other rows is fetched at most as padding
+    // of a batch of loads and dropped by a select.
+    const pz_status s1 = decode_attn_impl(cache, nullptr, nullptr, false, q, block_table, max_pages_per_seq, seq_lens,
+                                          batch, n_q_heads, sinks, sm_scale, k_scale, v_scale, window, split_tokens,
+                                          n_splits, ws, need, nullptr, out_dtype, hip_stream);
+    if (s1 != PZ_OK) return s1;
+    return pz_decode_attn_splitk_reduce(ws, need, batch, n_q_heads, cache->head_dim, n_splits, seq_lens, window,
+                                        split_tokens, sinks, v_scale, out, out_dtype, hip_stream);
+}
+
 pz_status pz_prefill_attn(const pz_cache *cache, const void *q, const int32_t *q_start,
                           const int32_t *block_table, int32_t max_pages_per_seq, const int32_t *seq_lens,
                           int32_t batch, int32_t n_q_heads, int32_t max_new_tokens, const float *sinks,
