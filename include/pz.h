@@ -192,11 +192,14 @@ pz_status pz_decode_attn(const pz_cache *cache /* host */, const void *q,
 /*
  * pz_kv_append_fp8 of one new token per sequence and pz_decode_attn in one call.  The paper's decode
  * step quantises the new token's K/V into the FP8 cache and then attends over the cache including
- * that token (Section 3, "KV Quantization"); this call does both, with the same arithmetic and the
- * same bytes as the two separate calls.  In single-pass calls, and in split-K calls of a few
- * sequences, the append runs inside the attention launch (one launch less per decode step: at decode
- * sizes the append is launch-bound); in larger split-K calls, where that is slower, the call enqueues
- * an append kernel of its own first -- it needs no slot mapping either way.
+ * that token (Section 3, "KV Quantization"); this call does both: the same cache bytes as the two
+ * separate calls, bit for bit, and the same attention.  Where it pays (single-pass calls, split-K calls of
+ * up to 1024 (sequence, KV head) pairs) the append runs inside the attention launch, one launch less per
+ * decode step: the wave that attends position L_b - 1 takes that position from k_new / v_new, quantised in
+ * registers, folds it into its online softmax as a last step of its own and writes the cache bytes when it
+ * is done -- the outputs then equal the separate calls' up to the rounding order of that one position (a
+ * few 1e-5 of the output RMS).  In larger split-K calls the call enqueues an append kernel of its own first
+ * (bit-identical outputs).  It needs no slot mapping either way.
  *
  *   k_new, v_new : bf16 [batch][n_kv_heads][head_dim]; row b is written to the slot of position
  *                  L_b - 1 of sequence b, i.e. block_table[b][(L_b-1)/page_size] * page_size +

@@ -188,15 +188,13 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     pz::AttnParams p;
     p.k = static_cast<uint8_t *>(cache->k);
     p.v = static_cast<uint8_t *>(cache->v);
-    // The append runs inside the attention launch for single-pass calls (short windows: batch 256, window 128
-    // takes 15 us that way against 18 us) and for split-K calls of a few sequences (up to 32 (sequence, KV
-    // head) pairs: batch 1 to 4 at 128K context each gain 2 us of 30 to 90).  In a larger split-K call the
-    // wave that attends the newest position is one of equally long, bandwidth-bound shares, and what it
-    // does besides (a dependent block-table read, 64 scattered V bytes) lengthens the whole launch by
-    // more than a launch of its own costs (batch 8 x 128K: + 5 us; batch 16, ragged: + 1 to 9 us; batch
-    // 256, window 8192: + 28 us), so there the token is appended by a launch of its own first: same
-    // bytes, same results.
-    bool in_kernel = fused_append && (split_tokens == 0 || (int64_t)batch * cache->n_kv_heads <= 32);
+    // The fused append runs inside the attention launch: the wave that attends the newest position takes it
+    // from k_new / v_new in registers, behind its step loop, and writes the cache bytes when it is done (batch
+    // 16 x 64K: 2 to 3 us less per step than with an append launch, batch 64 x 8K 2.4, batch 256 at window
+    // 128: 1.3).  Above 1024 (sequence, KV head) pairs in a split-K call it gets a launch of its own first
+    // instead: there every wave carries the extra round trip at its end and 64 scattered V bytes, which
+    // together cost more than the launch (batch 256 at window 8192: + 13 us of 338).  Same bytes either way.
+    bool in_kernel = fused_append && (split_tokens == 0 || (int64_t)batch * cache->n_kv_heads <= 1024);
     if (fused_append && pz::launch_override(PZ_OVERRIDE_APPEND_FUSED) >= 0)
         in_kernel = pz::launch_override(PZ_OVERRIDE_APPEND_FUSED) == 1;
     if (cache->n_kv_heads > 65535) in_kernel = fused_append;      // the append launch has one grid row per KV head

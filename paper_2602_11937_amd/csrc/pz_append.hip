@@ -25,16 +25,6 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-__device__ __forceinline__ float bf16_to_f32(unsigned bits16) { return __uint_as_float(bits16 << 16); }
-
-// two bf16 values packed in one dword -> two E4M3 codes in the low (hi=false) or high word of old
-__device__ __forceinline__ unsigned quant_pair(unsigned packed_bf16, float scale, unsigned old, bool hi) {
-    const float a = scaled_clamped(bf16_to_f32(packed_bf16 & 0xffffu), scale);
-    const float b = scaled_clamped(bf16_to_f32(packed_bf16 >> 16), scale);
-    return hi ? (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
-              : (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
-}
-
 template <int EB>
 __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams prm) {
     const int64_t t0 = (int64_t)blockIdx.x * 64;
@@ -54,10 +44,10 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
                 uint8_t *dst = prm.k + (((page * Hkv + g) * P + off) * 64 + part * 16) * EB;
                 if constexpr (EB == 1) {
                     u32x4 o;
-                    o[0] = quant_pair(x0[1], prm.k_scale, quant_pair(x0[0], prm.k_scale, 0u, false), true);
-                    o[1] = quant_pair(x0[3], prm.k_scale, quant_pair(x0[2], prm.k_scale, 0u, false), true);
-                    o[2] = quant_pair(x1[1], prm.k_scale, quant_pair(x1[0], prm.k_scale, 0u, false), true);
-                    o[3] = quant_pair(x1[3], prm.k_scale, quant_pair(x1[2], prm.k_scale, 0u, false), true);
+                    o[0] = quant4(x0[0], x0[1], prm.k_scale);
+                    o[1] = quant4(x0[2], x0[3], prm.k_scale);
+                    o[2] = quant4(x1[0], x1[1], prm.k_scale);
+                    o[3] = quant4(x1[2], x1[3], prm.k_scale);
                     *reinterpret_cast<u32x4 *>(dst) = o;
                 } else {
                     reinterpret_cast<u32x4 *>(dst)[0] = x0;

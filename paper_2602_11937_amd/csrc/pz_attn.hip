@@ -47,7 +47,6 @@ namespace {
 template <int P, int EB>
 __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
-    constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
     // dynamic LDS in records of 528 floats (8 heads x 64 channels, then 8 m's, then 8 l's):
     // one record per wave (n_waves > 1), or one for the group's partial (one-wave split-K)
     extern __shared__ float lds[];
@@ -153,122 +152,8 @@ __global__ __launch_bounds__(64 * kMaxWaves) void decode_attn_kernel(const pz::A
         const int n_steps = s_end - s_begin;
         const int s0 = s_begin + (int)(((int64_t)n_steps * wave) / n_waves);
         const int s1 = s_begin + (int)(((int64_t)n_steps * (wave + 1)) / n_waves);
-        if (s0 < s1) {
-            // Q^T operand: column n holds head n%8 of the group (zero beyond the group size)
-            bf16x8 qb[2];
-            {
-                u32x4 q0 = {0, 0, 0, 0}, q1 = {0, 0, 0, 0};
-                if (head < G) {
-                    const uint16_t *qrow = prm.q + ((int64_t)b * prm.Hq + qh) * 64 + 16 * kb;
-                    q0 = *reinterpret_cast<const u32x4 *>(qrow);
-                    q1 = *reinterpret_cast<const u32x4 *>(qrow + 8);
-                }
-                qb[0] = __builtin_bit_cast(bf16x8, q0);
-                qb[1] = __builtin_bit_cast(bf16x8, q1);
-            }
-            const unsigned lo_mask = (n >= 8) ? 0xffff0000u : 0u;
-            const LaneGeom geom = lane_geom<P, EB>(lane);
-            const int64_t page_bytes = (int64_t)prm.cache_heads * P * 64 * EB;
-            const uint8_t *kbase = prm.k + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
-            const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
-            const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
-            const float sc = prm.sc;
-
-            KTile<EB> kt;
-            VTile<EB> vt;
-            // The wave's steps are walked in groups whose page ids sit in two registers (lane i of
-            // ids0 / ids1 holds the physical page of page index pbase + i / pbase + 64 + i, clamped
-            // to attended pages).  Inside a group the K buffer is refilled right after QK^T has
-            // consumed it and the V buffer right after PV, unconditionally; the group's last step
-            // is peeled so that no load is conditional and every wait counts exactly the loads
-            // issued after the one needed.
-            for (int gs = s0; gs < s1; gs += GROUP) {
-                const int ge = min(gs + GROUP, s1);
-                const int pbase = gs * NPS;
-                int ids0, ids1;
-                if (early_ids && gs == s0) {           // s0 == early_s0 here
-                    const int last = pmax - pbase;     // >= 0: the group holds an attended position
-                    const int fix0 = __shfl(early0, min(last, 63));
-                    const int fix1 = __shfl(early1, min(max(last - 64, 0), 63));
-                    ids0 = lane <= last ? early0 : fix0;
-                    ids1 = last < 64 ? fix0 : (lane + 64 <= last ? early1 : fix1);
-                } else {
-                    ids0 = bt[min(max(pbase + lane, pmin), pmax)];
-                    ids1 = bt[min(max(pbase + 64 + lane, pmin), pmax)];
-                }
-                ids0 = bounded_page(ids0, prm.num_pages);
-                ids1 = bounded_page(ids1, prm.num_pages);
-                auto page_id = [&](int idx) -> int {   // idx: page index relative to pbase, < 128
-                    if constexpr (NPS == 1) {
-                        const int a = __builtin_amdgcn_readlane(ids0, idx & 63);
-                        const int c = __builtin_amdgcn_readlane(ids1, idx & 63);
-                        return idx < 64 ? a : c;
-                    } else {
-                        const int a = __shfl(ids0, idx & 63), c = __shfl(ids1, idx & 63);
-                        return idx < 64 ? a : c;
-                    }
-                };
-                auto k_page = [&](int s) -> const uint8_t * {
-                    return kbase + (int64_t)page_id(s * NPS + geom.kslot - pbase) * page_bytes;
-                };
-                auto v_page = [&](int s) -> const uint8_t * {
-                    return vbase + (int64_t)page_id(s * NPS + geom.vslot - pbase) * page_bytes;
-                };
-                auto step = [&](int s, bool prefetch) {
-                    const int base = s << 6;
-                    const bool full = base >= j0 && base + 64 <= j1;
-                    const unsigned valid = full ? 0xffffu : valid_mask(base + 16 * kb, j0, j1);
-                    f32x4 sacc[4];
-                    qk_step<EB>(kt, qb, sacc);
-                    if (prefetch) load_k<P, EB, EB == 1>(kt, k_page(s + 1), geom.koff);
-                    if (!full) {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r)
-                                sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
-                    }
-                    u32x4 pw[2];
-                    softmax_step(sacc, sc, lo_mask, st, pw);
-                    if (!full) mask_v<EB>(vt, valid);
-                    pv_step<EB>(vt, pw, st);
-                    if (prefetch) load_v<P, EB, EB == 1>(vt, v_page(s + 1), geom.voff);
-                };
-                load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
-                load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
-                // Fused append: the wave whose steps include position L - 1 writes the newest token's
-                // K/V (lane = channel) before it gets there.  It is placed after the first loads so
-                // that the block-table read it needs overlaps with them.  The writes and the later
-                // loads of the same bytes belong to this one wave and are kept in program order by
-                // the hardware; the explicit wait covers the case where that step is the first one.
-                if (gs == s0 && prm.k_new != nullptr && s1 > ((L - 1) >> 6) && j1 == L && prm.seq_lens[b] == L) {
-                    const int pos = L - 1;
-                    const int64_t page = bt[pos / P];
-                    const int off = pos % P;
-                    const int gc = g >> prm.head_shift;
-                    const int64_t src = ((int64_t)b * prm.cache_heads + gc) * 64 + lane;
-                    const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
-                    uint8_t *kd = prm.k + (((page * prm.cache_heads + gc) * P + off) * 64 + lane) * EB;
-                    uint8_t *vd = prm.v + (((page * prm.cache_heads + gc) * 64 + lane) * P + off) * EB;
-                    if (page < 0 || page >= prm.num_pages) {
-                        // a page the cache does not have: nothing is written
-                    } else if constexpr (EB == 1) {
-                        *kd = (uint8_t)quant_one(kb16, prm.k_scale);
-                        *vd = (uint8_t)quant_one(vb16, prm.v_scale);
-                    } else {
-                        *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
-                        *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
-                    }
-                    if (((L - 1) >> 6) == gs) {                    // the step just loaded holds position L - 1
-                        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-                        load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
-                        load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
-                    }
-                }
-                for (int s = gs; s + 1 < ge; ++s) step(s, true);
-                step(ge - 1, false);
-            }
-        }
+        if (s0 < s1)
+            run_steps<P, EB>(prm, st, bt, b, g, G, q_first, lane, L, lo, j0, j1, s0, s1, early_ids, early0, early1);
     }
 
     if (direct) {

@@ -49,7 +49,6 @@ __device__ __forceinline__ int wave_inclusive_scan_int(int x) {
 template <int P, int EB>
 __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::AttnParams prm) {
     constexpr int NPS = 64 / P;                        // pages per step
-    constexpr int GROUP = 128 / NPS;                   // steps whose page ids fit two registers
     __shared__ float lds[528];                         // a run's partial on its way out: 8 x 64 acc, 8 m, 8 l
 
     const int lane = threadIdx.x;
@@ -173,14 +172,6 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         c = max(c, 0);
     }
 
-    const unsigned lo_mask = (n >= 8) ? 0xffff0000u : 0u;
-    const LaneGeom geom = lane_geom<P, EB>(lane);
-    const int64_t page_bytes = (int64_t)prm.cache_heads * P * 64 * EB;
-    const uint8_t *kbase = prm.k + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
-    const uint8_t *vbase = prm.v + (int64_t)(g >> prm.head_shift) * P * 64 * EB;
-    const float sc = prm.sc;
-    const int qh = q_first + head;                       // only meaningful when head < G
-
     WaveState st;
     auto reset_state = [&]() {
         st.m = -INFINITY;
@@ -271,116 +262,11 @@ __global__ __launch_bounds__(64, 3) void decode_attn_balanced_kernel(const pz::A
         const int j0 = max(lo, a0 + c_first * split);
         const int j1 = (int)min((int64_t)L, (int64_t)a0 + (int64_t)c_last * split);
         const int s0 = j0 >> 6, s1 = (j1 + 63) >> 6;   // s0 < s1: every chunk of the list holds a position
-        const int pmin = lo / P, pmax = (L - 1) / P;   // pages that hold attended positions
-        const bool use_early = first_run && b == spec_b && c_first == spec_c;
+        const bool use_early = first_run && b == spec_b && c_first == spec_c;   // then s0 == spec_c * steps_per_chunk
         first_run = false;
-
-        // Q^T operand: column n holds head n%8 of the group (zero beyond the group size)
-        bf16x8 qb[2];
-        {
-            u32x4 q0 = {0, 0, 0, 0}, q1 = {0, 0, 0, 0};
-            if (head < G) {
-                const uint16_t *qrow = prm.q + ((int64_t)b * prm.Hq + qh) * 64 + 16 * kb;
-                q0 = *reinterpret_cast<const u32x4 *>(qrow);
-                q1 = *reinterpret_cast<const u32x4 *>(qrow + 8);
-            }
-            qb[0] = __builtin_bit_cast(bf16x8, q0);
-            qb[1] = __builtin_bit_cast(bf16x8, q1);
-        }
-
-        KTile<EB> kt;
-        VTile<EB> vt;
-        // Steps are walked in groups whose page ids sit in two registers; inside a group the K buffer is
-        // refilled right after QK^T has consumed it and the V buffer right after PV, unconditionally; the
-        // group's last step is peeled so that no load is conditional (see pz_attn.hip).
-        for (int gs = s0; gs < s1;) {
-            const int ge = min(gs + GROUP, s1);
-            const int pbase = gs * NPS;
-            int ids0, ids1;
-            if (use_early && gs == s0) {               // s0 == spec_c * steps_per_chunk here (window == 0)
-                const int last = pmax - pbase;         // >= 0: the group holds an attended position
-                const int fix0 = __shfl(early0, min(last, 63));
-                const int fix1 = __shfl(early1, min(max(last - 64, 0), 63));
-                ids0 = lane <= last ? early0 : fix0;
-                ids1 = last < 64 ? fix0 : (lane + 64 <= last ? early1 : fix1);
-            } else {
-                ids0 = bt[min(max(pbase + lane, pmin), pmax)];
-                ids1 = bt[min(max(pbase + 64 + lane, pmin), pmax)];
-            }
-            ids0 = bounded_page(ids0, prm.num_pages);
-            ids1 = bounded_page(ids1, prm.num_pages);
-            auto page_id = [&](int idx) -> int {       // idx: page index relative to pbase, < 128
-                if constexpr (NPS == 1) {
-                    const int a = __builtin_amdgcn_readlane(ids0, idx & 63);
-                    const int cc = __builtin_amdgcn_readlane(ids1, idx & 63);
-                    return idx < 64 ? a : cc;
-                } else {
-                    const int a = __shfl(ids0, idx & 63), cc = __shfl(ids1, idx & 63);
-                    return idx < 64 ? a : cc;
-                }
-            };
-            auto k_page = [&](int s) -> const uint8_t * {
-                return kbase + (int64_t)page_id(s * NPS + geom.kslot - pbase) * page_bytes;
-            };
-            auto v_page = [&](int s) -> const uint8_t * {
-                return vbase + (int64_t)page_id(s * NPS + geom.vslot - pbase) * page_bytes;
-            };
-            auto step = [&](int s, bool prefetch) {
-                const int base = s << 6;
-                const bool full = base >= j0 && base + 64 <= j1;
-                const unsigned valid = full ? 0xffffu : valid_mask(base + 16 * kb, j0, j1);
-                f32x4 sacc[4];
-                qk_step<EB>(kt, qb, sacc);
-                if (prefetch) load_k<P, EB, EB == 1>(kt, k_page(s + 1), geom.koff);
-                if (!full) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            sacc[j][r] = ((valid >> (4 * j + r)) & 1u) ? sacc[j][r] : -INFINITY;
-                }
-                u32x4 pw[2];
-                softmax_step(sacc, sc, lo_mask, st, pw);
-                if (!full) mask_v<EB>(vt, valid);
-                pv_step<EB>(vt, pw, st);
-                if (prefetch) load_v<P, EB, EB == 1>(vt, v_page(s + 1), geom.voff);
-            };
-            load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
-            load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
-            // Fused append (see pz_attn.hip): the run that reaches position L - 1 writes the newest
-            // token's K/V (lane = channel) after its first loads are on their way.
-            if (gs == s0 && prm.k_new != nullptr && j1 == L && prm.seq_lens[b] == L) {
-                const int pos = L - 1;
-                const int64_t page = bt[pos / P];
-                const int off = pos % P;
-                const int gc = g >> prm.head_shift;
-                const int64_t src = ((int64_t)b * prm.cache_heads + gc) * 64 + lane;
-                const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
-                uint8_t *kd = prm.k + (((page * prm.cache_heads + gc) * P + off) * 64 + lane) * EB;
-                uint8_t *vd = prm.v + (((page * prm.cache_heads + gc) * 64 + lane) * P + off) * EB;
-                if (page < 0 || page >= prm.num_pages) {
-                    // a page the cache does not have: nothing is written
-                } else if constexpr (EB == 1) {
-                    *kd = (uint8_t)quant_one(kb16, prm.k_scale);
-                    *vd = (uint8_t)quant_one(vb16, prm.v_scale);
-                } else {
-                    *reinterpret_cast<uint16_t *>(kd) = (uint16_t)kb16;
-                    *reinterpret_cast<uint16_t *>(vd) = (uint16_t)vb16;
-                }
-                if (((L - 1) >> 6) == gs) {            // the step just loaded holds position L - 1
-                    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-                    load_k<P, EB, EB == 1>(kt, k_page(gs), geom.koff);
-                    load_v<P, EB, EB == 1>(vt, v_page(gs), geom.voff);
-                }
-            }
-            for (int s = gs; s + 1 < ge; ++s) step(s, true);
-            step(ge - 1, false);
-            if (ge == s1) {                            // the run is done
-                park();
-                write_out(b, c_first, c_last);
-            }
-            gs = ge;
-        }
+        run_steps<P, EB>(prm, st, bt, b, g, G, q_first, lane, L, lo, j0, j1, s0, s1, use_early, early0, early1);
+        park();
+        write_out(b, c_first, c_last);
     }
 }
 

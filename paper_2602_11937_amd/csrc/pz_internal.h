@@ -41,8 +41,9 @@ struct AttnParams {
     float *ws_acc;               // split-K partials [B][Hq][S][64]
     float *ws_ml;                // [B][Hq][S][2]
     void *out;                   // [B][Hq][64]
-    // fused append (both nullptr: none): the newest token's K/V rows, bf16 [B][cache_heads][64]; the
-    // workgroup wave that attends position L_b - 1 writes them into the cache before it reads that step
+    // fused append (both nullptr: none): the newest token's K/V rows, bf16 [B][cache_heads][64].  The wave
+    // that attends position L_b - 1 takes them from here, quantised in registers, and writes them into the
+    // cache after its last step
     const uint16_t *k_new;
     const uint16_t *v_new;
     float k_scale;               // for the fused append only (the logits use sc)

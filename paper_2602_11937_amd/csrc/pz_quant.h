@@ -22,6 +22,19 @@ __device__ __forceinline__ unsigned quant_one(unsigned bits16, float scale) {
     return (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, a, 0, false) & 0xffu;
 }
 
+// two bf16 values packed in one dword -> two E4M3 codes in the low (hi=false) or high word of old
+__device__ __forceinline__ unsigned quant_pair(unsigned packed_bf16, float scale, unsigned old, bool hi) {
+    const float a = scaled_clamped(__uint_as_float(packed_bf16 << 16), scale);
+    const float b = scaled_clamped(__uint_as_float(packed_bf16 & 0xffff0000u), scale);
+    return hi ? (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, true)
+              : (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(a, b, (int)old, false);
+}
+
+// two dwords of packed bf16 pairs (4 values) -> 4 E4M3 codes in one dword, same element order
+__device__ __forceinline__ unsigned quant4(unsigned p0, unsigned p1, float scale) {
+    return quant_pair(p1, scale, quant_pair(p0, scale, 0u, false), true);
+}
+
 }  // namespace
 
 #endif

@@ -1,5 +1,11 @@
 """pz_decode_attn_append (the newest token's quantise-and-append fused into the attention launch)
-against the two separate calls: the same cache bytes and bit-identical outputs, and against the oracle."""
+against the two separate calls and against the oracle.  The cache bytes are the same bit for bit.  The
+outputs are bit-identical when the call appends by a launch of its own first; when the append runs inside
+the attention launch the newest position is folded into the online softmax last, as a step of its own,
+instead of together with the other positions of its 64-position step, so the same sums are rounded in
+another order: each weight enters as two truncated bf16 terms (2^-16 relative, one-sided) against a
+reference maximum that may differ between the two orders, plus fp32 roundings of the rescaling -- the two
+outputs agree to 1e-4 of the output RMS (measured: a few 1e-5), and each meets the bar against the oracle."""
 import numpy as np
 import pytest
 import torch
@@ -12,6 +18,14 @@ from helpers import oracle_cache, rel_err
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
+REGROUP = 1e-4         # fused-in-kernel against append-then-attend: rounding order of the online softmax only
+
+
+def same_outputs(out_a, out_b, way):
+    if way == "own_launch":
+        return torch.equal(out_a, out_b)
+    a, b = out_a.cpu().numpy(), out_b.cpu().numpy()
+    return not np.any(np.isnan(b)) and rel_err(b, a) <= REGROUP
 
 GEOMETRIES = {
     "p64_mixed": dict(B=5, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1500, 64, 65, 1, 129]),
@@ -77,7 +91,7 @@ def test_fused_equals_append_then_attention(name, split_tokens, fused_way):
     case = wl.make_case(name, seed=70 + len(name), **GEOMETRIES[name])
     (out_a, cache_a), (out_b, cache_b) = run_pair(case, split_tokens)
     assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v)     # canary bytes included
-    assert torch.equal(out_a, out_b)
+    assert same_outputs(out_a, out_b, fused_way)
     kc, vc = oracle_cache(case)
     gk, gv = to_oracle_layout(cache_b)
     assert np.array_equal(gk, kc) and np.array_equal(gv, vc)
@@ -90,17 +104,20 @@ def test_fused_append_into_a_bf16_cache(fused_way):
     case = wl.make_case("b", B=3, Hq=16, Hkv=2, d=64, P=32, seq_lens=[200, 32, 33], seed=81)
     for split in (0, 128):
         (out_a, cache_a), (out_b, cache_b) = run_pair(case, split, dtype=pz.KV_BF16)
-        assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v) and torch.equal(out_a, out_b)
+        assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v)
+        assert same_outputs(out_a, out_b, fused_way)
 
 
 @pytest.mark.parametrize("waves,cpg", [(1, 1), (1, 3), (2, 1), (4, 1), (8, 1)])
 def test_fused_append_under_every_launch_shape(waves, cpg, launch_override):
+    launch_override("append_fused", 1)
     launch_override("attn_waves", waves)
     launch_override("attn_chunks_per_group", cpg)
     case = wl.make_case("s", B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[3000, 64, 700, 1], seed=82)
     for split in (0, 256):
         (out_a, cache_a), (out_b, cache_b) = run_pair(case, split)
-        assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v) and torch.equal(out_a, out_b)
+        assert torch.equal(cache_a.k, cache_b.k) and torch.equal(cache_a.v, cache_b.v)
+        assert same_outputs(out_a, out_b, "in_kernel")
 
 
 def test_a_decode_loop_of_fused_steps_matches_the_oracle(fused_way):

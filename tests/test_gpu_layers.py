@@ -109,5 +109,5 @@ def test_the_36_layer_step_matches_the_oracle_layer_by_layer(kv):
             worst = max(worst, err)
         outs[fused] = [x.out.cpu().numpy() for _, x in sides]
         print("36-layer step, %s cache, fused=%s: worst layer error %.2e of output RMS" % (kv, fused, worst))
-    for a, c in zip(outs[False], outs[True]):                        # the fused form computes the same
-        assert np.array_equal(a, c)
+    for a, c in zip(outs[False], outs[True]):      # the fused form: the same sums in another rounding order
+        assert rel_err(c, a) <= 1e-4
