@@ -187,3 +187,51 @@ def test_launch_override_entry_takes_only_its_listed_values():
     blob = open(pz.lib_path(), "rb").read()
     for name in (b"PZ_ATTN_WAVES", b"PZ_APPEND_FORM", b"PZ_APPEND_FUSED", b"PZ_ATTN_BALANCED", b"getenv"):
         assert name not in blob, name
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """include/pz.h compiles as C99 with nothing but <stddef.h> / <stdint.h>, and a C program that calls the
+    host-side entry points links against libpz.so and gets the documented values (no GPU involved)."""
+    import subprocess
+    src = tmp_path / "use_pz.c"
+    src.write_text(r'''
+#include "pz.h"
+#include <stdio.h>
+int main(void) {
+    pz_cache c = {0};
+    if (pz_decode_attn_n_splits(65536, 0, 1024) != 64) return 1;
+    if (pz_decode_attn_workspace_bytes(16, 64, 64, 64) != (size_t)16 * 64 * 64 * 66 * 4) return 2;
+    if (pz_window_pages(8192, 64) != 129) return 3;
+    if (pz_kv_append_fp8(&c, 0, 0, 0, 1, 1.0f, 1.0f, 0) != PZ_ERR_NULL) return 4;       /* refused on the host */
+    if (pz_decode_attn_noalloc(0, 0, 0, 1, 0, 1, 8, 0, 1.f, 1.f, 1.f, 0, 64, 1, (void *)8, PZ_OUT_F32, 0) != PZ_ERR_NULL) return 5;
+    if (pz_debug_set_launch_override(PZ_OVERRIDE_COUNT, 1) != PZ_ERR_SHAPE) return 6;
+    if (PZ_NOALLOC_WORKSPACE_BYTES != (32u << 20)) return 7;
+    printf("%s\n", pz_status_string(PZ_ERR_WORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_pz"
+    lib_dir = os.path.dirname(pz.lib_path())
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                        "-o", str(exe), "-L", lib_dir, "-l:libpz.so", "-Wl,-rpath," + lib_dir],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0 and "WORKSPACE" in r.stdout, (r.returncode, r.stdout, r.stderr)
+
+
+def test_bench_reports_counter_traffic_only_for_the_sources_it_was_measured_on(tmp_path, monkeypatch):
+    import bench
+    kernel = "decode_attn_balanced_kernel<64,1>"
+    got, why = bench.traffic_from_profile("cfg3", kernel)
+    line = [l for l in open(os.path.join(ROOT, "profiles", "decode_step_cfg3_fp8_hbm_traffic.txt")) if l.startswith("bench.py reads:")]
+    assert len(line) == 1
+    recorded = re.search(r"source_sha256=([0-9a-f]+)", line[0]).group(1)
+    if recorded == bench.kernel_source_hash():
+        assert got == int(re.search(r"traffic_bytes_per_launch=(\d+)", line[0]).group(1)) and "profiles/" in why
+    else:
+        assert got is None and "measure again" in why
+    monkeypatch.setattr(bench, "kernel_source_hash", lambda: "0" * 16)
+    got, why = bench.traffic_from_profile("cfg3", kernel)
+    assert got is None and "measure again" in why
+    assert bench.traffic_from_profile("cfg4_w128", kernel)[0] is None

@@ -79,3 +79,42 @@ def test_bf16_output_and_the_size_limit():
     assert st == 0
     ref = gpu_attn(case, cache, split_tokens=64, sinks=None, n_splits=fits)
     assert np.array_equal(out.cpu().numpy(), ref)
+
+
+def test_recorded_into_a_hip_graph_and_replayed():
+    """What the entry point is for: a capture in which nothing may allocate.  The first call on the device is
+    made eagerly (it looks up the array's address); the captured call then only enqueues kernels, and every
+    replay -- with other calls of the same entry point, on other sizes, between the replays -- gives the eager
+    result."""
+    case = wl.make_case("cap", B=4, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1500, 64, 700, 129], seed=320)
+    other = wl.make_case("cap2", B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[300, 2000], seed=321)
+    cache, cache2 = gpu_cache(case), gpu_cache(other)
+    q, bt = dev_bits(case.q), torch.from_numpy(case.block_table).to(DEV)
+    sl, sinks = torch.from_numpy(case.seq_lens).to(DEV), torch.from_numpy(case.sinks).to(DEV)
+    split = 256
+    S = pz.pz_decode_attn_n_splits(1500, 0, split)
+    out = torch.zeros((case.B, case.Hq, case.d), dtype=torch.float32, device=DEV)
+
+    def call():
+        pz.pz_decode_attn_noalloc(cache, q, bt, case.max_pages, sl, case.B, case.Hq, sinks, case.sm_scale, case.k_scale,
+                                  case.v_scale, 0, split, S, out)
+
+    call()
+    torch.cuda.synchronize()
+    eager = out.clone()
+    assert np.array_equal(eager.cpu().numpy(), gpu_attn(case, cache, split_tokens=split))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(3):
+        out.fill_(float("nan"))
+        st, got2 = noalloc_attn(other, cache2, 0, 128)             # leaves other partials in the array
+        assert st == 0 and np.array_equal(got2, gpu_attn(other, cache2, split_tokens=128))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), i
