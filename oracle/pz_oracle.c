@@ -33,8 +33,15 @@
  * Pins (tests/test_oracle_*.py): E4M3 codec against torch.float8_e4m3fn and a nearest-value
  * search in exact arithmetic; attention against a dense float64 numpy softmax; closed forms for
  * L = 1, q = 0, equal keys; window >= L == full; sink = -inf == plain softmax; chunked partials
- * merged == unsplit.  Model-level accuracy effects of the scales (paper Table 4) are
- * "parity unpinned": they need weights and benchmark suites that are not available.
+ * merged == unsplit; rotary tables against plain rotary embedding at factor 1 and the defining
+ * properties of the YaRN blend.
+ * "parity unpinned" (readings that nothing the paper prints can confirm; their tests restate the
+ * reading): the sink semantics (the paper only cites sink attention; the logit-in-the-denominator
+ * form is the parent model's public definition); of pzo_yarn_table everything beyond the factor
+ * 56 -- the temperature 0.1 ln(factor) + 1 and the constants theta, beta_fast, beta_slow and
+ * original context, which are the published YaRN rule with the parent's public configuration
+ * (Section 2 gives only the change of the factor from 32 to 56); model-level accuracy effects of
+ * the scales (paper Table 4), which need weights and benchmark suites that are not available.
  */
 #include <math.h>
 #include <pthread.h>
