@@ -286,7 +286,13 @@ def oracle_sample(oracle, torch, layer, seqs):
     newest token of each sequence.  Returns (kc, vc, block_table, q_bits, new_k, new_v, new_slots)."""
     lay = layer.lay
     P = lay.P
-    off, fp = lay.ctx_offsets, lay.first_pos
+    off, fp0 = lay.ctx_offsets, lay.first_pos
+    # a window layer never attends to positions before its window: the oracle's copy starts at the page that
+    # holds the window's first position (the entries before it stay -1)
+    fp = np.array(fp0, dtype=np.int64)
+    if layer.window > 0:
+        L64 = lay.seq_lens.astype(np.int64)
+        fp = np.maximum(fp, (np.maximum(L64 - layer.window, 0) // P) * P)
     end_page = [-(-int(lay.seq_lens[b]) // P) for b in seqs]
     bt = np.full((len(seqs), max(end_page)), -1, dtype=np.int32)
     at = 0
@@ -297,8 +303,9 @@ def oracle_sample(oracle, torch, layer, seqs):
     kc, vc = oracle.new_cache(at * P, lay.Hkv, lay.d, oracle.KV_FP8)
     new_k, new_v, new_slots = [], [], []
     for i, b in enumerate(seqs):
-        kb = lay.k_ctx[off[b]:off[b + 1]].view(torch.int16).cpu().numpy().view(np.uint16)
-        vb = lay.v_ctx[off[b]:off[b + 1]].view(torch.int16).cpu().numpy().view(np.uint16)
+        skip = int(fp[b] - fp0[b])                  # resident rows of the sequence that lie before the window
+        kb = lay.k_ctx[off[b] + skip:off[b + 1]].view(torch.int16).cpu().numpy().view(np.uint16)
+        vb = lay.v_ctx[off[b] + skip:off[b + 1]].view(torch.int16).cpu().numpy().view(np.uint16)
         j = np.arange(int(fp[b]), int(lay.seq_lens[b]), dtype=np.int64)
         slots = bt[i, j // P].astype(np.int64) * P + j % P
         oracle.kv_append(kc, vc, kb[:-1], vb[:-1], slots[:-1], lay.k_scale, lay.v_scale)
@@ -349,7 +356,8 @@ def run_layer_workload(args, pz, wl, torch, name, light=False):
     if args.cpu_seqs is not None:
         cpu_seqs = args.cpu_seqs
     else:
-        cpu_seqs = spec["B"] if name in ("cfg3", "cfg2") and not light else min(spec["B"], 8)
+        whole = name in ("cfg3", "cfg2", "cfg4_w128") or (name == "cfg4_w8192" and not light)
+        cpu_seqs = spec["B"] if whole else min(spec["B"], 32 if name == "cfg4_w8192" else 8)
     if args.calib_copy:
         src = torch.ones((768 << 20) // 4, dtype=torch.int32, device="cuda")
         dst = torch.empty_like(src)

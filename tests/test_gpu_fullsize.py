@@ -25,8 +25,10 @@ def oracle_sequences(layer, seqs):
     oracle.kv_append(kc, vc, new_k, new_v, new_slots, lay.k_scale, lay.v_scale)
     for i, b in enumerate(seqs):
         # the GPU cache bytes of the resident positions, read through the block table, are the oracle's
-        L, fp = int(lay.seq_lens[b]), int(lay.first_pos[b])
-        p0, p1 = fp // P, -(-L // P)
+        L = int(lay.seq_lens[b])
+        p0, p1 = int(np.argmax(bt[i] >= 0)), -(-L // P)      # the oracle's copy starts at the window's first page
+        fp = p0 * P
+        assert fp >= int(lay.first_pos[b]) and (layer.window == 0 or fp <= max(L - layer.window, 0))
         pages = torch.from_numpy(lay.block_table_host[b, p0:p1].astype(np.int64)).cuda()
         gk = layer.cache.k[pages].permute(0, 2, 1, 3).reshape(-1, lay.Hkv, lay.d)[:L - fp].cpu().numpy()
         gv = layer.cache.v[pages].permute(0, 3, 1, 2).reshape(-1, lay.Hkv, lay.d)[:L - fp].cpu().numpy()
@@ -42,8 +44,8 @@ def oracle_sequences(layer, seqs):
 # then compared on both sides of the crossing.
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("name,seqs", [("cfg3", list(range(16))), ("cfg2", list(range(64))),
-                                       ("cfg4_w128", list(range(96, 128)) + [0, 255]),
-                                       ("cfg4_w8192", list(range(96, 112)) + [0, 255]),
+                                       ("cfg4_w128", list(range(256))),
+                                       ("cfg4_w8192", list(range(64, 128)) + [0, 255]),
                                        ("cfg5_w128", list(range(32))), ("cfg5_w8192", list(range(8, 20)) + [0, 31]),
                                        ("cfg5_full", list(range(4, 12)) + [31])])
 def test_bench_configuration_against_oracle_on_sampled_sequences(name, seqs):
