@@ -67,6 +67,10 @@ WORKLOADS = {
                          text="diagnostic: batch 8 x context 131072, split-K 1024"),
     "diag_b16_ragged": dict(B=16, L=(1024, 131072), window=0, split_tokens=1024, outlier_frac=0.0, seed=5, instances=4,
                             text="diagnostic: batch 16, ragged contexts U[1024,131072], split-K 1024"),
+    # what one GPU of a tensor-parallel group of 8 holds of cfg3: one KV head and its 8 query heads
+    "diag_tp8_shard": dict(B=16, L=65536, window=0, split_tokens=1024, outlier_frac=0.01, seed=3, instances=8, Hq=8, Hkv=1,
+                           text="diagnostic: cfg3 sharded over KV heads for tensor parallelism 8 (1 KV head + 8 query heads "
+                                "per GPU): batch 16 x context 65536, split-K 1024"),
     # single layers of the heterogeneous step (cfg5), for tests and tuning
     "cfg5_full": dict(B=32, L=(1024, 131072), window=0, split_tokens=CFG5_SPLIT, outlier_frac=0.0, seed=5, instances=3,
                       bounded=True, text="cfg5 full-attention layer: batch 32, ragged contexts U[1024,131072], split-K %d" % CFG5_SPLIT),
@@ -141,8 +145,8 @@ class Layer:
         self.kv_dtype = kv_dtype
         # a window layer keeps only the pages its window can touch (spec["bounded"])
         resident = self.window + 64 if (spec.get("bounded") and self.window > 0) else None
-        lay = wl.device_layer(B=B, seq_lens=seq_lens, window=self.window, seed=seed,
-                              outlier_frac=spec["outlier_frac"], resident=resident)
+        lay = wl.device_layer(B=B, Hq=spec.get("Hq", 64), Hkv=spec.get("Hkv", 8), seq_lens=seq_lens, window=self.window,
+                              seed=seed, outlier_frac=spec["outlier_frac"], resident=resident)
         self.lay = lay
         self.k_scale = lay.k_scale if kv_dtype == pz.KV_FP8 else 1.0
         self.v_scale = lay.v_scale if kv_dtype == pz.KV_FP8 else 1.0
@@ -386,7 +390,7 @@ def run_layer_workload(args, pz, wl, torch, name, light=False):
         "value": step_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
         "steps": steps, "warmup": warmup, "ms_per_step": ms_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
-        "config": {"workload": spec["text"], "batch": B, "n_q_heads": 64, "n_kv_heads": 8, "head_dim": 64,
+        "config": {"workload": spec["text"], "batch": B, "n_q_heads": spec.get("Hq", 64), "n_kv_heads": spec.get("Hkv", 8), "head_dim": 64,
                    "page_size": 64, "window": spec["window"], "split_tokens": spec["split_tokens"],
                    "cache_instances_rotated": len(layers)},
         "attn_tokens_per_s": B / (ms_step * 1e-3),
