@@ -78,3 +78,32 @@ def test_outlier_channels_raise_the_k_scale():
     a = wl.make_case("a", B=1, Hq=8, Hkv=2, d=64, P=16, seq_lens=[256], seed=9)
     b = wl.make_case("b", B=1, Hq=8, Hkv=2, d=64, P=16, seq_lens=[256], seed=9, outlier_frac=0.05)
     assert len(b.extra["outlier_pairs"]) == 6 and b.k_scale > 5 * a.k_scale
+
+
+def test_layer_gains_scale_the_calibrated_scales():
+    """k_gain / v_gain multiply K / V before the rounding to bf16, so the max-calibrated scales follow them
+    (layers of a model differ in activation magnitude); a power-of-two gain scales the values exactly."""
+    import workloads as wl
+    a = wl.make_case("g", B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[40, 9], seed=3)
+    b = wl.make_case("g", B=2, Hq=8, Hkv=2, d=64, P=16, seq_lens=[40, 9], seed=3, k_gain=4.0, v_gain=0.25)
+    assert np.array_equal(wl.bf16_to_f32(b.k), 4.0 * wl.bf16_to_f32(a.k))
+    assert np.array_equal(wl.bf16_to_f32(b.v), 0.25 * wl.bf16_to_f32(a.v))
+    assert b.k_scale == 4.0 * a.k_scale and b.v_scale == 0.25 * a.v_scale
+    assert np.array_equal(a.q, b.q) and np.array_equal(a.block_table, b.block_table)
+
+
+def test_decode_step_sizes_one_workspace_for_the_whole_stack():
+    """DecodeStep (the per-layer loop) shares one split-K workspace: as large as the hungriest layer needs, with
+    every layer's chunk count from the library's own helper; single-pass layers need none."""
+    import torch
+    import paper_2602_11937_amd as pz
+    from paper_2602_11937_amd.decode_step import DecodeLayer, DecodeStep
+    cache = pz.PagedCache(k=None, v=None, num_pages=1, page_size=64, n_kv_heads=8, head_dim=64)
+    def layer(window, split):
+        return DecodeLayer(cache=cache, block_table=None, max_pages=1, window=window, k_scale=1.0, v_scale=1.0,
+                           sm_scale=0.125, sinks=None, split_tokens=split)
+    layers = [layer(128, 0), layer(8192, 1024), layer(0, 1024), layer(0, 8192)]
+    step = DecodeStep(layers, batch=4, n_q_heads=64, max_seq_len=70000, device="cpu")
+    assert step.n_splits == [0, 9, 69, 9]
+    assert step.ws_bytes == [0] + [pz.pz_decode_attn_workspace_bytes(4, 64, 64, s) for s in (9, 69, 9)]
+    assert step.workspace.numel() * 4 == max(step.ws_bytes) and step.workspace.dtype == torch.float32
