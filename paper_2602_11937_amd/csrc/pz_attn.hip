@@ -282,7 +282,8 @@ __device__ __forceinline__ float wave_sum(float x) {
 // batch is a dependent round trip to memory, so they are spread over waves) the waves' running
 // (M, numerator, denominator) meet in LDS and wave 0, which also carries the sink, finishes.
 // NB = chunks per batch (64, or 16 for rows of at most 16 chunks so that a short row does not issue 64 loads).
-template <int W, int NB>
+// LAZY: the accumulator rows are fetched after the (m, l) pairs, only those that hold a partial.
+template <int W, int NB, bool LAZY = false>
 __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
@@ -302,8 +303,10 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
         if (lane < cnt) v = ml[base + lane];
         const float *a = acc + (int64_t)base * 64 + lane;
         float x[NB];
+        if constexpr (!LAZY) {
 #pragma unroll
-        for (int u = 0; u < NB; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
+            for (int u = 0; u < NB; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
+        }
         if (first && prm.seq_lens != nullptr) {        // chunks past this bound were never written
             const int L = bounded_len(prm.seq_lens[b], 1 << 30);   // keeps the sums below in 32 bits
             const int lo = (prm.window > 0 && L > prm.window) ? L - prm.window : 0;
@@ -319,6 +322,27 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
         num *= keep;
         den = den * keep + wave_sum(v.y * w);
         M = M_new;
+        if constexpr (LAZY) {
+            // only the rows that hold a partial are fetched, eight at a time (all eight loads in flight)
+            uint64_t live = __ballot(w != 0.f && base + lane < n);
+            while (live != 0) {
+                int idx[8];
+                float xv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    idx[e] = live != 0 ? __builtin_ctzll(live) : -1;
+                    if (live != 0) live &= live - 1;
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xv[e] = __builtin_nontemporal_load(a + (int64_t)max(idx[e], 0) * 64);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float we = __shfl(w, max(idx[e], 0));
+                    num = __builtin_fmaf(idx[e] >= 0 ? xv[e] : 0.f, idx[e] >= 0 ? we : 0.f, num);
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
             const float wu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w), u));
@@ -385,10 +409,20 @@ hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
     // one wave per 64 chunks, at most eight; short rows in one batch of 16
     const dim3 grid((unsigned)(prm.B * prm.Hq));
     if (prm.n_splits <= 16) return launch(splitk_reduce_kernel<1, 16>, grid, dim3(64), 0, stream, prm);
-    if (prm.n_splits <= 64) return launch(splitk_reduce_kernel<1, 64>, grid, dim3(64), 0, stream, prm);
-    if (prm.n_splits <= 128) return launch(splitk_reduce_kernel<2, 64>, grid, dim3(128), 0, stream, prm);
-    if (prm.n_splits <= 256) return launch(splitk_reduce_kernel<4, 64>, grid, dim3(256), 0, stream, prm);
-    return launch(splitk_reduce_kernel<8, 64>, grid, dim3(512), 0, stream, prm);
+    // A job this large was walked by one-wave workgroups that each merged a run of chunks in registers (at
+    // least 2048 (sequence, KV head, chunk) items whatever the group size), so most rows are empty markers:
+    // the accumulator rows are then asked for once the (m, l) pairs show which ones hold a partial -- a
+    // dependent round trip instead of 64 row loads per lane of which 56 are dropped (batch 16 x 64K:
+    // 171.9 -> 170.0 us per step, batch 32 x 64K 328.8 -> 324.2).  Smaller jobs have a partial in every row
+    // and fetch everything at once.
+    const bool lazy = (int64_t)prm.B * prm.Hq * prm.n_splits >= 16384;
+#define PZ_REDUCE(W) (lazy ? launch(splitk_reduce_kernel<W, 64, true>, grid, dim3(64 * W), 0, stream, prm) \
+                           : launch(splitk_reduce_kernel<W, 64, false>, grid, dim3(64 * W), 0, stream, prm))
+    if (prm.n_splits <= 64) return PZ_REDUCE(1);
+    if (prm.n_splits <= 128) return PZ_REDUCE(2);
+    if (prm.n_splits <= 256) return PZ_REDUCE(4);
+    return PZ_REDUCE(8);
+#undef PZ_REDUCE
 }
 
 }  // namespace pz
