@@ -79,3 +79,21 @@ def test_chunked_prefill_equals_one_shot():
         got, _ = gpu_prefill(part, cache, q[done - n:done], [n], 100)
         rows.append(got)
     assert rel_err(np.concatenate(rows), want) < 1e-5
+
+
+@pytest.mark.parametrize("window", [0, 700])
+@pytest.mark.parametrize("kv", ["fp8", "bf16"])
+def test_long_prompt_on_both_cache_dtypes(window, kv):
+    """Hundreds of query tokens per sequence (many column tiles, a ragged last one), a window that starts
+    inside the prompt, and the BF16 cache variant of the same kernel."""
+    case = wl.make_case("pl", B=2, Hq=16, Hkv=2, d=64, P=64, seq_lens=[1500, 333], seed=21)
+    if kv == "bf16":
+        case = wl.Case(**{**case.__dict__, "k_scale": 1.0, "v_scale": 1.0})
+    n_new = [517, 333]
+    cache = gpu_cache(case, dtype=pz.KV_BF16 if kv == "bf16" else pz.KV_FP8)
+    kc, vc = oracle_cache(case, oracle.KV_BF16 if kv == "bf16" else oracle.KV_FP8)
+    q = wl.bf16_bits(np.random.default_rng(5).standard_normal((sum(n_new), case.Hq, case.d)).astype(np.float32))
+    got, q_start = gpu_prefill(case, cache, q, n_new, window)
+    want = oracle.prefill_attn(kc, vc, case.P, q, q_start, case.block_table, case.seq_lens, case.sinks,
+                               case.sm_scale, case.k_scale, case.v_scale, window, accum="f64", nthreads=8)
+    assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL
