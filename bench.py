@@ -71,6 +71,9 @@ WORKLOADS = {
     "diag_tp8_shard": dict(B=16, L=65536, window=0, split_tokens=1024, outlier_frac=0.01, seed=3, instances=8, Hq=8, Hkv=1,
                            text="diagnostic: cfg3 sharded over KV heads for tensor parallelism 8 (1 KV head + 8 query heads "
                                 "per GPU): batch 16 x context 65536, split-K 1024"),
+    # 128-channel heads (not the paper's model: the boundary's second head dimension), as many KV bytes as cfg3
+    "diag_d128": dict(B=16, L=32768, window=0, split_tokens=1024, outlier_frac=0.0, seed=11, instances=4, d=128,
+                      text="diagnostic: head dimension 128: batch 16 x context 32768, 64 q / 8 KV heads, split-K 1024"),
     # single layers of the heterogeneous step (cfg5), for tests and tuning
     "cfg5_full": dict(B=32, L=(1024, 131072), window=0, split_tokens=CFG5_SPLIT, outlier_frac=0.0, seed=5, instances=3,
                       bounded=True, text="cfg5 full-attention layer: batch 32, ragged contexts U[1024,131072], split-K %d" % CFG5_SPLIT),
@@ -145,7 +148,8 @@ class Layer:
         self.kv_dtype = kv_dtype
         # a window layer keeps only the pages its window can touch (spec["bounded"])
         resident = self.window + 64 if (spec.get("bounded") and self.window > 0) else None
-        lay = wl.device_layer(B=B, Hq=spec.get("Hq", 64), Hkv=spec.get("Hkv", 8), seq_lens=seq_lens, window=self.window,
+        lay = wl.device_layer(B=B, Hq=spec.get("Hq", 64), Hkv=spec.get("Hkv", 8), d=spec.get("d", 64), seq_lens=seq_lens,
+                              window=self.window,
                               seed=seed, outlier_frac=spec["outlier_frac"], resident=resident)
         self.lay = lay
         self.k_scale = lay.k_scale if kv_dtype == pz.KV_FP8 else 1.0
@@ -383,6 +387,8 @@ def run_layer_workload(args, pz, wl, torch, name, light=False):
     kern_avg_ms = float(kern_ms.mean())
     kernel = "decode_attn_balanced_kernel<64,1>" if spec["window"] == 0 and spec["split_tokens"] > 0 \
         else "decode_attn_kernel<64,1>"
+    if spec.get("d", 64) == 128:
+        kernel = "decode_attn_d128_kernel<64,1>"
     traffic, traffic_note = (None, "split_tokens overridden") if (args.split_tokens is not None and not light) \
         else traffic_from_profile(name, kernel)
     result = {

@@ -27,7 +27,11 @@
  *     buffers whose sizes the calls do not take.)
  *   - Positions are 32-bit: max_pages_per_seq * page_size may not exceed 2^30 and
  *     n_splits * split_tokens must stay below 2^31 (PZ_ERR_UNSUPPORTED otherwise).
- *   - Supported shapes: head_dim == 64; page_size in {16, 32, 64}; n_q_heads a multiple of
+ *   - Supported shapes: head_dim == 64 (the parent model's; every entry point), or 128 for
+ *     pz_kv_append_fp8, pz_decode_attn, pz_decode_attn_append (which then always appends by a launch
+ *     of its own), pz_decode_attn_splitk_reduce and pz_decode_attn_noalloc -- one plain launch form,
+ *     not the tuned path; pz_prefill_attn and pz_rope_kv_append_fp8 return PZ_ERR_UNSUPPORTED for it.
+ *     page_size in {16, 32, 64}; n_q_heads a multiple of
  *     n_kv_heads with group size n_q_heads / n_kv_heads <= 64 (a group above 8 is cut into 2, 4
  *     or 8 parts of at most 8 heads and the attention kernels read each KV head once per part).
  *

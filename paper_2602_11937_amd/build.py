@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpz.so")
-SOURCES = ["pz_api.hip", "pz_attn.hip", "pz_attn_balanced.hip", "pz_append.hip", "pz_calib.hip", "pz_pages.hip", "pz_rope.hip", "pz_prefill.hip"]
+SOURCES = ["pz_api.hip", "pz_attn.hip", "pz_attn_balanced.hip", "pz_attn_d128.hip", "pz_append.hip", "pz_calib.hip", "pz_pages.hip", "pz_rope.hip", "pz_prefill.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-fast-math",

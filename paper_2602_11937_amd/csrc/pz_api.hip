@@ -14,11 +14,13 @@ std::atomic<int> g_override[PZ_OVERRIDE_COUNT] = {{-1}, {-1}, {-1}, {-1}, {-1}};
 
 bool supported_page(int p) { return p == 16 || p == 32 || p == 64; }
 
-pz_status check_cache(const pz_cache *c) {
+// wide: the entry point also takes a head dimension of 128 (append, decode attention, merge); prefill and
+// the rotary append are for 64-channel heads
+pz_status check_cache(const pz_cache *c, bool wide = false) {
     if (c == nullptr || c->k == nullptr || c->v == nullptr) return PZ_ERR_NULL;
     if (c->num_pages <= 0 || c->page_size <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0) return PZ_ERR_SHAPE;
     if (c->dtype != PZ_KV_FP8_E4M3 && c->dtype != PZ_KV_BF16) return PZ_ERR_UNSUPPORTED;
-    if (c->head_dim != 64 || !supported_page(c->page_size)) return PZ_ERR_UNSUPPORTED;
+    if (!(c->head_dim == 64 || (wide && c->head_dim == 128)) || !supported_page(c->page_size)) return PZ_ERR_UNSUPPORTED;
     return PZ_OK;
 }
 
@@ -111,7 +113,7 @@ const char *pz_status_string(pz_status s) {
 pz_status pz_kv_append_fp8(const pz_cache *cache, const void *k_new, const void *v_new,
                            const int64_t *slot_mapping, int64_t n_tokens, float k_scale,
                            float v_scale, void *hip_stream) {
-    const pz_status cs = check_cache(cache);
+    const pz_status cs = check_cache(cache, true);
     if (cs != PZ_OK) return cs;
     if (n_tokens < 0) return PZ_ERR_SHAPE;
     if (n_tokens == 0) return PZ_OK;
@@ -128,6 +130,7 @@ pz_status pz_kv_append_fp8(const pz_cache *cache, const void *k_new, const void 
     p.T = n_tokens;
     p.Hkv = cache->n_kv_heads;
     p.P = cache->page_size;
+    p.D = cache->head_dim;
     p.num_slots = cache->num_pages * (int64_t)cache->page_size;
     p.k_scale = k_scale;
     p.v_scale = v_scale;
@@ -159,8 +162,9 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
                            float v_scale, int32_t window, int32_t split_tokens, int32_t n_splits,
                            void *workspace, size_t workspace_bytes, void *out, int32_t out_dtype,
                            void *hip_stream) {
-    const pz_status cs = check_cache(cache);
+    const pz_status cs = check_cache(cache, true);
     if (cs != PZ_OK) return cs;
+    const bool wide = cache->head_dim == 128;
     if (batch < 0 || n_q_heads <= 0 || max_pages_per_seq <= 0 || window < 0 || split_tokens < 0)
         return PZ_ERR_SHAPE;
     if (n_q_heads % cache->n_kv_heads != 0) return PZ_ERR_SHAPE;
@@ -198,6 +202,10 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     if (fused_append && pz::launch_override(PZ_OVERRIDE_APPEND_FUSED) >= 0)
         in_kernel = pz::launch_override(PZ_OVERRIDE_APPEND_FUSED) == 1;
     if (cache->n_kv_heads > 65535) in_kernel = fused_append;      // the append launch has one grid row per KV head
+    if (wide) {                                                   // 128-channel heads: always a launch of its own
+        if (fused_append && cache->n_kv_heads > 65535) return PZ_ERR_UNSUPPORTED;
+        in_kernel = false;
+    }
     p.k_new = in_kernel ? static_cast<const uint16_t *>(k_new) : nullptr;
     p.v_new = in_kernel ? static_cast<const uint16_t *>(v_new) : nullptr;
     p.k_scale = k_scale;
@@ -240,6 +248,10 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
         full_chunks = full_chunks < 1 ? 1 : (full_chunks > n_chunks ? n_chunks : full_chunks);
     }
     pick_shape(batch, p.Hkv, max_steps, n_chunks, full_chunks, &n_waves, &chunks_per_group);
+    if (wide && n_waves > 1) {                                    // one-wave workgroups only: one chunk each then
+        n_waves = 1;
+        chunks_per_group = 1;
+    }
     p.chunks_per_group = chunks_per_group;
     const int elem_bytes = cache->dtype == PZ_KV_FP8_E4M3 ? 1 : 2;
     hipError_t e;
@@ -253,6 +265,7 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
         a.T = batch;
         a.Hkv = cache->n_kv_heads;
         a.P = cache->page_size;
+        a.D = cache->head_dim;
         a.num_slots = cache->num_pages * (int64_t)cache->page_size;
         a.k_scale = k_scale;
         a.v_scale = v_scale;
@@ -266,7 +279,9 @@ pz_status decode_attn_impl(const pz_cache *cache, const void *k_new, const void 
     // first and last chunks are short, which a partition by chunk count does not see, and a share that
     // crosses from one short sequence into the next starts its pipeline anew each time (batch 256,
     // window 8192: 373 us on the balanced partition against 355 us on the grid).
-    if (split_tokens > 0 && window == 0 && n_waves == 1 && pz::launch_override(PZ_OVERRIDE_ATTN_BALANCED) != 0)
+    if (wide)
+        e = pz::launch_decode_attn_d128(p, cache->page_size, elem_bytes, static_cast<hipStream_t>(hip_stream));
+    else if (split_tokens > 0 && window == 0 && n_waves == 1 && pz::launch_override(PZ_OVERRIDE_ATTN_BALANCED) != 0)
         e = pz::launch_decode_attn_balanced(p, cache->page_size, elem_bytes, static_cast<hipStream_t>(hip_stream));
     else
         e = pz::launch_decode_attn(p, cache->page_size, elem_bytes, n_waves, static_cast<hipStream_t>(hip_stream));
@@ -303,7 +318,7 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
                                        const float *sinks, float v_scale, void *out, int32_t out_dtype,
                                        void *hip_stream) {
     if (batch < 0 || n_q_heads <= 0 || head_dim <= 0 || n_splits <= 0 || window < 0) return PZ_ERR_SHAPE;
-    if (head_dim != 64) return PZ_ERR_UNSUPPORTED;
+    if (head_dim != 64 && head_dim != 128) return PZ_ERR_UNSUPPORTED;
     if (out_dtype != PZ_OUT_F32 && out_dtype != PZ_OUT_BF16) return PZ_ERR_UNSUPPORTED;
     if (seq_lens != nullptr && (split_tokens <= 0 || split_tokens % 64 != 0)) return PZ_ERR_SHAPE;
     if (seq_lens != nullptr && split_tokens > kMaxPositions) return PZ_ERR_UNSUPPORTED;
@@ -326,6 +341,7 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
     p.window = window;
     p.split_tokens = split_tokens;
     p.out_dtype = out_dtype;
+    p.head_dim = head_dim;
     p.v_scale = v_scale;
     const hipError_t e = pz::launch_splitk_reduce(p, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? PZ_OK : PZ_ERR_LAUNCH;
@@ -493,6 +509,7 @@ pz_status pz_rope_kv_append_fp8(const pz_cache *cache, const void *q_in, void *q
     p.ap.T = n_tokens;
     p.ap.Hkv = cache->n_kv_heads;
     p.ap.P = cache->page_size;
+    p.ap.D = cache->head_dim;
     p.ap.num_slots = cache->num_pages * (int64_t)cache->page_size;
     p.ap.k_scale = k_scale;
     p.ap.v_scale = v_scale;

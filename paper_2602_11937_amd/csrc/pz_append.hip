@@ -6,14 +6,15 @@
 //
 // Three launch forms, the same bytes:
 //   tile form (large appends: cache builds, prompts): one workgroup = up to 64 tokens of one KV head.
-//     K ([page][head][P][64]): 4 threads per token, 16 channels each -> one 16-byte store; the 16
+//     K ([page][head][P][d]): 4 threads per token, 16 channels each -> one 16-byte store; the 16
 //       tokens of a wave write 16 x 64 B rows (contiguous when their slots are).
-//     V ([page][head][64][P]): lane = token, each wave walks 16 channels -> byte stores that are
+//     V ([page][head][d][P]): lane = token, each wave walks 16 channels -> byte stores that are
 //       contiguous across the lanes of a wave when the tokens' slots are contiguous.
 //   token form (decode-sized appends): one wave per (token, KV head), lane = channel.
 //   last-token form (split-K calls of pz_decode_attn_append): as the token form, placed from the block
 //     table and the sequence lengths instead of a slot mapping.
-// Tokens whose slot (or page) lies outside the cache are skipped in every form.
+// Tokens whose slot (or page) lies outside the cache are skipped in every form.  A head dimension of 128
+// ([page][head][P][128] / [page][head][128][P]) runs every form once per 64-channel half (grid z).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -30,18 +31,19 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
     const int64_t t0 = (int64_t)blockIdx.x * 64;
     const int g = blockIdx.y;
     const int P = prm.P, Hkv = prm.Hkv;
+    const int D = prm.D, c_half = 64 * blockIdx.z;     // this workgroup's 64 channels
 
     {   // ---- K: thread = (token, 16-channel part)
         const int64_t t = t0 + (threadIdx.x >> 2);
         const int part = threadIdx.x & 3;
         if (t < prm.T) {
             // the row is fetched beside the slot, not after it: one memory round trip, not two
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(prm.k_new + (t * Hkv + g) * 64 + part * 16);
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(prm.k_new + (t * Hkv + g) * D + c_half + part * 16);
             const u32x4 x0 = src[0], x1 = src[1];
             const int64_t slot = prm.slot_mapping[t];
             if (slot >= 0 && slot < prm.num_slots) {
                 const int64_t page = slot / P, off = slot % P;
-                uint8_t *dst = prm.k + (((page * Hkv + g) * P + off) * 64 + part * 16) * EB;
+                uint8_t *dst = prm.k + (((page * Hkv + g) * P + off) * D + c_half + part * 16) * EB;
                 if constexpr (EB == 1) {
                     u32x4 o;
                     o[0] = quant4(x0[0], x0[1], prm.k_scale);
@@ -58,9 +60,9 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
     }
     {   // ---- V: lane = token, wave = 16-channel part
         const int64_t t = t0 + (threadIdx.x & 63);
-        const int c0 = (threadIdx.x >> 6) * 16;
+        const int c0 = c_half + (threadIdx.x >> 6) * 16;
         if (t < prm.T) {
-            const uint16_t *src = prm.v_new + (t * Hkv + g) * 64 + c0;
+            const uint16_t *src = prm.v_new + (t * Hkv + g) * D + c0;
             // plain loads: the four waves of a workgroup read neighbouring 32-byte pieces of the same rows,
             // which only the caches turn into whole-line traffic (a streaming hint cost 45 % here)
             const u32x4 x0 = reinterpret_cast<const u32x4 *>(src)[0];
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
             const int64_t slot = prm.slot_mapping[t];
             if (slot >= 0 && slot < prm.num_slots) {
                 const int64_t page = slot / P, off = slot % P;
-                uint8_t *dst = prm.v + (((page * Hkv + g) * 64 + c0) * P + off) * EB;
+                uint8_t *dst = prm.v + (((page * Hkv + g) * D + c0) * P + off) * EB;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const unsigned w = (i < 8) ? x0[i / 2] : x1[(i - 8) / 2];
@@ -86,9 +88,9 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const pz::AppendParams p
 template <int EB>
 __device__ __forceinline__ void put_token(const pz::AppendParams &prm, int64_t page, int off, int g, int c,
                                           unsigned kb16, unsigned vb16) {
-    const int P = prm.P, Hkv = prm.Hkv;
-    uint8_t *kd = prm.k + (((page * Hkv + g) * P + off) * 64 + c) * EB;
-    uint8_t *vd = prm.v + (((page * Hkv + g) * 64 + c) * P + off) * EB;
+    const int P = prm.P, Hkv = prm.Hkv, D = prm.D;
+    uint8_t *kd = prm.k + (((page * Hkv + g) * P + off) * D + c) * EB;
+    uint8_t *vd = prm.v + (((page * Hkv + g) * D + c) * P + off) * EB;
     if constexpr (EB == 1) {
         *kd = (uint8_t)quant_one(kb16, prm.k_scale);
         *vd = (uint8_t)quant_one(vb16, prm.v_scale);
@@ -103,8 +105,8 @@ __device__ __forceinline__ void put_token(const pz::AppendParams &prm, int64_t p
 template <int EB>
 __global__ __launch_bounds__(64) void kv_append_token_kernel(const pz::AppendParams prm) {
     const int64_t t = blockIdx.x;
-    const int g = blockIdx.y, c = threadIdx.x;
-    const int64_t src = (t * prm.Hkv + g) * 64 + c;
+    const int g = blockIdx.y, c = 64 * blockIdx.z + threadIdx.x;
+    const int64_t src = (t * prm.Hkv + g) * prm.D + c;
     const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
     const int64_t slot = prm.slot_mapping[t];
     if (slot < 0 || slot >= prm.num_slots) return;
@@ -117,9 +119,9 @@ template <int EB>
 __global__ __launch_bounds__(64) void kv_append_last_kernel(const pz::AppendParams prm,
                                                             const int32_t *__restrict__ block_table, int max_pages,
                                                             const int32_t *__restrict__ seq_lens) {
-    const int b = blockIdx.x, g = blockIdx.y, c = threadIdx.x;
+    const int b = blockIdx.x, g = blockIdx.y, c = 64 * blockIdx.z + threadIdx.x;
     const int L = seq_lens[b];
-    const int64_t src = ((int64_t)b * prm.Hkv + g) * 64 + c;
+    const int64_t src = ((int64_t)b * prm.Hkv + g) * prm.D + c;
     const unsigned kb16 = prm.k_new[src], vb16 = prm.v_new[src];
     if (L <= 0 || L > max_pages * prm.P) return;           // no token, or a length the table row does not cover
     const int pos = L - 1;
@@ -134,7 +136,7 @@ namespace pz {
 
 hipError_t launch_kv_append_last(const AppendParams &prm, const int32_t *block_table, int max_pages,
                                  const int32_t *seq_lens, int batch, int elem_bytes, hipStream_t stream) {
-    const dim3 grid((unsigned)batch, (unsigned)prm.Hkv), block(64);
+    const dim3 grid((unsigned)batch, (unsigned)prm.Hkv, (unsigned)(prm.D / 64)), block(64);
     if (elem_bytes == 1) return launch(kv_append_last_kernel<1>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
     return launch(kv_append_last_kernel<2>, grid, block, 0, stream, prm, block_table, max_pages, seq_lens);
 }
@@ -144,11 +146,11 @@ hipError_t launch_kv_append(const AppendParams &prm, int elem_bytes, hipStream_t
     const int form = launch_override(PZ_OVERRIDE_APPEND_FORM);
     const bool token_form = form >= 0 ? form == 1 : prm.T * prm.Hkv <= 8192;
     if (token_form && prm.T <= 0x7fffffff) {
-        const dim3 grid((unsigned)prm.T, (unsigned)prm.Hkv), block(64);
+        const dim3 grid((unsigned)prm.T, (unsigned)prm.Hkv, (unsigned)(prm.D / 64)), block(64);
         if (elem_bytes == 1) return launch(kv_append_token_kernel<1>, grid, block, 0, stream, prm);
         return launch(kv_append_token_kernel<2>, grid, block, 0, stream, prm);
     }
-    const dim3 grid((unsigned)((prm.T + 63) / 64), (unsigned)prm.Hkv), block(256);
+    const dim3 grid((unsigned)((prm.T + 63) / 64), (unsigned)prm.Hkv, (unsigned)(prm.D / 64)), block(256);
     if (elem_bytes == 1) return launch(kv_append_kernel<1>, grid, block, 0, stream, prm);
     return launch(kv_append_kernel<2>, grid, block, 0, stream, prm);
 }

@@ -283,13 +283,14 @@ __device__ __forceinline__ float wave_sum(float x) {
 // (M, numerator, denominator) meet in LDS and wave 0, which also carries the sink, finishes.
 // NB = chunks per batch (64, or 16 for rows of at most 16 chunks so that a short row does not issue 64 loads).
 // LAZY: the accumulator rows are fetched after the (m, l) pairs, only those that hold a partial.
-template <int W, int NB, bool LAZY = false>
+// D: head dimension; with 128 a second grid row of workgroups merges channels 64..127 the same way.
+template <int W, int NB, bool LAZY = false, int D = 64>
 __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceParams prm) {
     const int row = blockIdx.x;                        // b * Hq + h
     const int b = row / prm.Hq, h = row % prm.Hq;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int S = prm.n_splits;
-    const float *acc = prm.ws_acc + (int64_t)row * S * 64;
+    const float *acc = prm.ws_acc + (int64_t)row * S * D + (D > 64 ? 64 * (int)blockIdx.y : 0);
     const float2 *ml = reinterpret_cast<const float2 *>(prm.ws_ml) + (int64_t)row * S;
     const float sink = (prm.sinks != nullptr && wave == 0) ? prm.sinks[h] : -INFINITY;
     float M = sink;                                    // running reference maximum
@@ -301,11 +302,11 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
         const int cnt = min(NB, S - base);             // rows that exist
         float2 v = {-INFINITY, 0.f};
         if (lane < cnt) v = ml[base + lane];
-        const float *a = acc + (int64_t)base * 64 + lane;
+        const float *a = acc + (int64_t)base * D + lane;
         float x[NB];
         if constexpr (!LAZY) {
 #pragma unroll
-            for (int u = 0; u < NB; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * 64);
+            for (int u = 0; u < NB; ++u) x[u] = __builtin_nontemporal_load(a + (int64_t)min(u, cnt - 1) * D);
         }
         if (first && prm.seq_lens != nullptr) {        // chunks past this bound were never written
             const int L = bounded_len(prm.seq_lens[b], 1 << 30);   // keeps the sums below in 32 bits
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
                     if (live != 0) live &= live - 1;
                 }
 #pragma unroll
-                for (int e = 0; e < 8; ++e) xv[e] = __builtin_nontemporal_load(a + (int64_t)max(idx[e], 0) * 64);
+                for (int e = 0; e < 8; ++e) xv[e] = __builtin_nontemporal_load(a + (int64_t)max(idx[e], 0) * D);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float we = __shfl(w, max(idx[e], 0));
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(64 * W) void splitk_reduce_kernel(const pz::ReduceP
         }
     }
     const float r = (den > 0.f) ? prm.v_scale * num / den : 0.f;
-    store_out(prm.out, prm.out_dtype, (int64_t)row * 64 + lane, r);
+    store_out(prm.out, prm.out_dtype, (int64_t)row * D + (D > 64 ? 64 * (int)blockIdx.y : 0) + lane, r);
 }
 
 }  // namespace
@@ -407,6 +408,14 @@ hipError_t launch_decode_attn(const AttnParams &prm, int page_size, int elem_byt
 
 hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
     // one wave per 64 chunks, at most eight; short rows in one batch of 16
+    if (prm.head_dim == 128) {
+        const dim3 grid((unsigned)(prm.B * prm.Hq), 2);
+        if (prm.n_splits <= 16) return launch(splitk_reduce_kernel<1, 16, false, 128>, grid, dim3(64), 0, stream, prm);
+        if (prm.n_splits <= 64) return launch(splitk_reduce_kernel<1, 64, false, 128>, grid, dim3(64), 0, stream, prm);
+        if (prm.n_splits <= 128) return launch(splitk_reduce_kernel<2, 64, false, 128>, grid, dim3(128), 0, stream, prm);
+        if (prm.n_splits <= 256) return launch(splitk_reduce_kernel<4, 64, false, 128>, grid, dim3(256), 0, stream, prm);
+        return launch(splitk_reduce_kernel<8, 64, false, 128>, grid, dim3(512), 0, stream, prm);
+    }
     const dim3 grid((unsigned)(prm.B * prm.Hq));
     if (prm.n_splits <= 16) return launch(splitk_reduce_kernel<1, 16>, grid, dim3(64), 0, stream, prm);
     // A job this large was walked by one-wave workgroups that each merged a run of chunks in registers (at

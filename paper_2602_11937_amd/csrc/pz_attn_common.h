@@ -101,13 +101,15 @@ struct LaneGeom {
     unsigned koff, voff;     // byte offset of the lane's first piece inside the page tile
 };
 
-template <int P, int EB>
+// D = head dimension: the row pitch of a K tile.  A 128-channel head is two 64-channel halves: the pieces of
+// half h lie 64 * EB bytes further along a K row and 64 * P * EB bytes further into a V tile.
+template <int P, int EB, int D = 64>
 __device__ __forceinline__ LaneGeom lane_geom(int lane) {
     const int t = lane & 15, kb = lane >> 4;
     LaneGeom g;
     const int krow0 = 16 * (t >> 2) + (t & 3);        // position (within the step) of K tile 0
     g.kslot = krow0 / P;
-    g.koff = (unsigned)((krow0 % P) * 64 * EB + kb * 16 * EB);
+    g.koff = (unsigned)((krow0 % P) * D * EB + kb * 16 * EB);
     const int vtok0 = 16 * kb;                         // first of the lane's 16 positions
     g.vslot = vtok0 / P;
     g.voff = (unsigned)(t * P * EB + (vtok0 % P) * EB);
@@ -125,13 +127,13 @@ __device__ __forceinline__ u32x4 load16(const uint8_t *__restrict__ p) {
 }
 
 // K: tile j holds rows 16*(t/4) + 4*j + (t%4) of the step: +4 rows per j
-template <int P, int EB, bool STREAM = false>
+template <int P, int EB, bool STREAM = false, int D = 64>
 __device__ __forceinline__ void load_k(KTile<EB> &tile, const uint8_t *__restrict__ kpage, unsigned koff) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int e = 0; e < EB; ++e)
-            tile.k[j * EB + e] = load16<STREAM>(kpage + koff + j * (4 * 64 * EB) + e * 16);
+            tile.k[j * EB + e] = load16<STREAM>(kpage + koff + j * (4 * D * EB) + e * 16);
 }
 
 // V: channel tile c holds channels 16*c + t: +16 rows of P elements per c

@@ -11,11 +11,13 @@
 
 namespace {
 
-struct WaveState {
+template <int NO>
+struct WaveStateT {
     float m;          // running maximum of the log2-scaled logits of this lane's head column
     f32x4 l;          // denominator share of the lane's column (P half), every element the same
-    f32x4 o[4];       // O^T: channel 16*c + 4*kb + r of the lane's head column
+    f32x4 o[NO];      // O^T: channel 16*c + 4*kb + r of the lane's head column (NO = head dimension / 16)
 };
+typedef WaveStateT<4> WaveState;
 
 // S^T tiles of one step: sacc[j][r] = raw dot product of position 16*kb + 4*j + r with head column n
 template <int EB>
@@ -29,7 +31,8 @@ __device__ __forceinline__ void qk_step(const KTile<EB> &tile, const bf16x8 (&qb
 }
 
 // Online softmax of one step for the lane's head column; returns the packed P^T operands.
-__device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigned lo_mask, WaveState &st,
+template <int NO>
+__device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigned lo_mask, WaveStateT<NO> &st,
                                              u32x4 (&pw)[2]) {
     float mx = fmax3(sacc[0][0], sacc[0][1], sacc[0][2]);
     mx = fmax3(mx, sacc[0][3], sacc[1][0]);
@@ -52,7 +55,7 @@ __device__ __forceinline__ void softmax_step(f32x4 (&sacc)[4], float sc, unsigne
             p[4 * j + r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j][r], sc, -m_new));
     if (__any(alpha != 1.0f)) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) st.o[c] *= alpha;
+        for (int c = 0; c < NO; ++c) st.o[c] *= alpha;
         st.l *= alpha;
     }
     // P^T operand: head columns 0..7 take the top bf16 of p, columns 8..15 the remainder

@@ -32,9 +32,9 @@ inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t
 int launch_override(int which);
 
 struct AttnParams {
-    uint8_t *k;                  // K cache  [page][Hkv][P][64]   (written only by the fused append)
-    uint8_t *v;                  // V cache  [page][Hkv][64][P]
-    const uint16_t *q;           // bf16 [B][Hq][64]
+    uint8_t *k;                  // K cache  [page][Hkv][P][d]   (written only by the fused append); d = 64 or 128
+    uint8_t *v;                  // V cache  [page][Hkv][d][P]
+    const uint16_t *q;           // bf16 [B][Hq][d]
     const int32_t *block_table;  // [B][max_pages]
     const int32_t *seq_lens;     // [B]
     const float *sinks;          // [Hq] or nullptr
@@ -63,6 +63,8 @@ struct AttnParams {
 };
 
 hipError_t launch_decode_attn_balanced(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream);
+// head dimension 128 (pz_attn_d128.hip): one-wave workgroups per (sequence, KV head, chunk group)
+hipError_t launch_decode_attn_d128(const AttnParams &prm, int page_size, int elem_bytes, hipStream_t stream);
 
 // Balanced partition of `tot` chunks of one KV head over at most `bph` workgroups: n_act shares, the
 // first r of q + 1 chunks, the others of q.  The share size aimed at is the smallest that leaves at
@@ -94,6 +96,7 @@ struct ReduceParams {
     const float *sinks;          // or nullptr
     void *out;
     int32_t B, Hq, n_splits, window, split_tokens, out_dtype;
+    int32_t head_dim;            // 64 or 128: row length of ws_acc and of out
     float v_scale;
 };
 
@@ -106,6 +109,7 @@ struct AppendParams {
     int64_t T;
     int64_t num_slots;           // num_pages * P: tokens whose slot is not in [0, num_slots) are skipped
     int32_t Hkv, P;
+    int32_t D;                   // head dimension, 64 or 128 (the kernels then run once per 64-channel half)
     float k_scale, v_scale;
 };
 

@@ -60,7 +60,8 @@ def test_decode_attn_rejects_bad_arguments_before_any_launch():
     assert attn(cache(k=None)) == NULL
     assert attn(cache(), q=None) == NULL and attn(cache(), seq_lens=None) == NULL
     assert attn(cache(), out=None) == NULL
-    assert attn(cache(head_dim=128)) == UNSUP and attn(cache(page_size=48)) == UNSUP
+    assert attn(cache(head_dim=96)) == UNSUP and attn(cache(head_dim=256)) == UNSUP and attn(cache(page_size=48)) == UNSUP
+    assert attn(cache(head_dim=128), batch=0) == 0                   # 128-channel heads are taken
     assert attn(cache(dtype=7)) == UNSUP
     assert attn(cache(), n_q_heads=60) == SHAPE                      # not a multiple of the KV heads
     assert attn(cache(n_kv_heads=1), n_q_heads=65) == UNSUP          # groups above 64
@@ -99,7 +100,7 @@ def test_fused_append_call_validates_like_the_plain_call():
 
     assert fused(cache(), k_new=None) == NULL and fused(cache(), v_new=None) == NULL
     assert fused(cache(), q=None) == NULL and fused(None) == NULL
-    assert fused(cache(), n_q_heads=60) == SHAPE and fused(cache(head_dim=128)) == UNSUP
+    assert fused(cache(), n_q_heads=60) == SHAPE and fused(cache(head_dim=256)) == UNSUP
     assert fused(cache(), k_scale=0.0) == SHAPE
     assert fused(cache(), batch=0) == 0
 
@@ -124,7 +125,7 @@ def test_append_and_reduce_reject_bad_arguments():
                                                a["seq_lens"], a["window"], a["split"], a["sinks"], a["vs"],
                                                a["out"], a["odt"], stream=0, check=False)
     assert red(ws=None) == -4 and red(wsb=10) == -4
-    assert red(out=None) == -1 and red(d=128) == -3 and red(S=0) == -2
+    assert red(out=None) == -1 and red(d=96) == -3 and red(d=128, batch=0) == 0 and red(S=0) == -2
     assert red(seq_lens=0x30, split=0) == -2 and red(vs=0.0) == -2
     assert red(seq_lens=0x30, split=(1 << 30) + 64) == -3
     assert red(batch=0) == 0
@@ -132,7 +133,7 @@ def test_append_and_reduce_reject_bad_arguments():
 
 def test_error_wrapper_raises():
     with pytest.raises(pz.PzError) as e:
-        pz.pz_decode_attn(cache(head_dim=128), 1, 1, 1, 1, 1, 8, None, 1, 1, 1, 0, 0, 0, None, 0, 1, stream=0)
+        pz.pz_decode_attn(cache(head_dim=96), 1, 1, 1, 1, 1, 8, None, 1, 1, 1, 0, 0, 0, None, 0, 1, stream=0)
     assert e.value.status == -3
 
 
@@ -153,7 +154,7 @@ def test_new_entry_points_reject_bad_arguments():
                                         a["slots"], a["n"], a["hq"], a["ks"], a["vs"], stream=0, check=False)
     assert rope(None) == -1 and rope(c, pos=None) == -1 and rope(c, cos=None) == -1 and rope(c, q_out=None) == -1
     assert rope(c, n=-1) == -2 and rope(c, ks=0.0) == -2 and rope(c, n=0) == 0
-    assert rope(cache(head_dim=128)) == -3
+    assert rope(cache(head_dim=128)) == -3                                  # the rotary append is for 64-channel heads
     # prefill
     def pre(cc, **kw):
         a = dict(q=0x10, qs=0x20, bt=0x30, mp=4, sl=0x40, b=2, hq=64, mx=16, sinks=None, sm=0.125, ks=0.01, vs=0.01,
@@ -164,6 +165,7 @@ def test_new_entry_points_reject_bad_arguments():
     assert pre(None) == -1 and pre(c, qs=None) == -1 and pre(c, out=None) == -1
     assert pre(c, hq=60) == -2 and pre(c, mx=-1) == -2 and pre(c, sm=0.0) == -2
     assert pre(cache(n_kv_heads=1), hq=65) == -3 and pre(c, odt=5) == -3    # a group of 65 heads
+    assert pre(cache(head_dim=128)) == -3                                   # so is prefill
     assert pre(c, b=0) == 0 and pre(c, mx=0) == 0
     assert pre(cache(page_size=64), mp=(1 << 24) + 1) == -3                 # more than 2^30 positions per row
     # page pool
