@@ -129,7 +129,7 @@ def merge_runs_of_partials(oacc, oml, starts):
     return np.array(lse), np.array(avg)
 
 
-def check_workspace_rows(acc, ml, oacc, oml, tol):
+def check_workspace_rows(acc, ml, oacc, oml, tol, lse_tol=1e-4):
     """The split-K workspace of the GPU path ([B][Hq][S][d] and [B][Hq][S][2]) against the oracle's
     per-chunk partials.  A row is unwritten (chunk without an attended position), empty (m = -inf,
     l = 0: its chunk was merged into an earlier row) or holds the partial of the run of chunks from
@@ -147,7 +147,9 @@ def check_workspace_rows(acc, ml, oacc, oml, tol):
         the test cases keep the sum below 10 for the positions that carry weight: 4e-5;
       * the hardware exp2 (1 ulp), the rescaling of l by exp2(m_old - m_new) once per 64 positions
         (a rounding each, at most 128 of them in these cases) and m * ln 2 in fp32: 1.5e-5 together.
-    The three add up to 8.6e-5 in the worst case, all signs aligned."""
+    The three add up to 8.6e-5 in the worst case, all signs aligned.  With 128-channel heads a logit is a
+    sum of 128 products ((128 + 3) * 2^-24 = 7.8e-6 per unit of a sum that stays below 10: 7.8e-5), 1.24e-4 in
+    all: those cases pass lse_tol = 1.5e-4."""
     B, Hq, S, _ = acc.shape
     n_partials = 0
     worst_avg, worst_lse = 0.0, 0.0
@@ -170,6 +172,6 @@ def check_workspace_rows(acc, ml, oacc, oml, tol):
             rms = float(np.sqrt(np.mean(avg_o ** 2)))
             worst_avg = max(worst_avg, float(np.max(np.abs(avg_g - avg_o))) / (rms if rms > 0 else 1.0))
             n_partials += len(starts)
-    assert worst_lse < 1e-4, worst_lse
+    assert worst_lse < lse_tol, worst_lse
     assert worst_avg <= tol, worst_avg
     return n_partials

@@ -68,7 +68,7 @@ def test_workspace_rows_and_chunk_groups(cpg, launch_override):
         S = acc.shape[2]
         oacc, oml = oracle.decode_attn_partials(kc, vc, case.P, case.q, case.block_table, case.seq_lens, case.sm_scale,
                                                 case.k_scale, window, 128, S, accum="f64")
-        assert check_workspace_rows(acc, ml, oacc, oml, TOL) >= case.B * case.Hq
+        assert check_workspace_rows(acc, ml, oacc, oml, TOL, lse_tol=1.5e-4) >= case.B * case.Hq
         assert rel_err(got, oracle_out(case, kc, vc, window=window)) <= TOL
 
 
