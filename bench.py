@@ -41,8 +41,9 @@ METRIC = "decode-attention GB/s (% of HBM peak) + attn tokens/s, B=16 ctx=64K FP
 HBM_PEAK_GBPS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 DTYPE = "e4m3 KV -> bf16 MFMA operands, f32 accumulate"
-CFG5_SPLIT = 8192      # split-K chunk length of cfg5's full and window-8192 layers (the configuration names none;
-                       # 8192 measured best: 1024 4.17 ms, 2048 4.03, 4096 3.81, 8192 3.77, 16384 4.11)
+CFG5_SPLIT = 8192      # split-K chunk length of cfg5's full and window-8192 layers (the configuration names none).
+                       # Per step at 1024 / 2048 / 4096 / 8192 / 16384: a full layer 314.4 / 312.8 / 312.8 / 311.3 /
+                       # 386.2 us, a window-8192 layer 50.9 / 51.4 / 50.9 / 50.1 / 49.1 us
 
 WORKLOADS = {
     # name: (B, seq_lens spec, window, split_tokens, outlier_frac, seed, instances, description)
