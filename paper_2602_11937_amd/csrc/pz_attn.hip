@@ -279,7 +279,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 // register (uniform lane index).  A wave's first batch is fetched before the sequence length is
 // known; rows of chunks beyond the sequence (which the first pass does not write) are inside the
 // workspace, so the read is safe, and they are discarded.  With W > 1 (more than 64 chunks: each
-// batch is a dependent round trip to memory, so they are spread over waves) the waves' running
+// batch is a dependent round trip to memory, so they are spread over four or eight waves) the waves' running
 // (M, numerator, denominator) meet in LDS and wave 0, which also carries the sink, finishes.
 // NB = chunks per batch (64, or 16 for rows of at most 16 chunks so that a short row does not issue 64 loads).
 // LAZY: the accumulator rows are fetched after the (m, l) pairs, only those that hold a partial.
@@ -412,7 +412,6 @@ hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
         const dim3 grid((unsigned)(prm.B * prm.Hq), 2);
         if (prm.n_splits <= 16) return launch(splitk_reduce_kernel<1, 16, false, 128>, grid, dim3(64), 0, stream, prm);
         if (prm.n_splits <= 64) return launch(splitk_reduce_kernel<1, 64, false, 128>, grid, dim3(64), 0, stream, prm);
-        if (prm.n_splits <= 128) return launch(splitk_reduce_kernel<2, 64, false, 128>, grid, dim3(128), 0, stream, prm);
         if (prm.n_splits <= 256) return launch(splitk_reduce_kernel<4, 64, false, 128>, grid, dim3(256), 0, stream, prm);
         return launch(splitk_reduce_kernel<8, 64, false, 128>, grid, dim3(512), 0, stream, prm);
     }
@@ -427,8 +426,12 @@ hipError_t launch_splitk_reduce(const ReduceParams &prm, hipStream_t stream) {
     const bool lazy = (int64_t)prm.B * prm.Hq * prm.n_splits >= 16384;
 #define PZ_REDUCE(W) (lazy ? launch(splitk_reduce_kernel<W, 64, true>, grid, dim3(64 * W), 0, stream, prm) \
                            : launch(splitk_reduce_kernel<W, 64, false>, grid, dim3(64 * W), 0, stream, prm))
+    // Never two waves per workgroup: a grid of two-wave workgroups leaves the chip in a state in which the
+    // one-wave workgroups of the attention launch that follows are placed unevenly over the SIMDs (that launch
+    // then took 11 to 13 us longer: ragged batch 32 at 1024-token chunks 325 -> 312 us per attention + merge,
+    // batch 8 x 128K 174 -> 168); one, four and eight waves per workgroup do not.  65 to 128 chunks therefore
+    // run on four waves, two of them idle.
     if (prm.n_splits <= 64) return PZ_REDUCE(1);
-    if (prm.n_splits <= 128) return PZ_REDUCE(2);
     if (prm.n_splits <= 256) return PZ_REDUCE(4);
     return PZ_REDUCE(8);
 #undef PZ_REDUCE
