@@ -45,14 +45,15 @@ ROUTES = {
 }
 
 
+@pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("P", [16, 64])
 @pytest.mark.parametrize("route", sorted(ROUTES))
-def test_attention_with_hostile_tables_and_lengths(route, P, launch_override):
+def test_attention_with_hostile_tables_and_lengths(route, P, d, launch_override):
     r = ROUTES[route]
     for name, value in r.get("force", {}).items():
         launch_override(name, value)
     window = r.get("window", 0)
-    case = wl.make_case("h", B=5, Hq=8, Hkv=2, d=64, P=P, seq_lens=[300, 517, 130, 260, 411], seed=70 + P, window=window)
+    case = wl.make_case("h", B=5, Hq=8, Hkv=2, d=d, P=P, seq_lens=[300, 517, 130, 260, 411], seed=70 + P, window=window)
     cache = gpu_cache(case)
     kc, vc = oracle_cache(case)
     want = oracle.decode_attn(kc, vc, case.P, case.q, case.block_table, case.seq_lens, sinks=case.sinks,
@@ -70,11 +71,12 @@ def test_attention_with_hostile_tables_and_lengths(route, P, launch_override):
     assert np.array_equal(gk, kc) and np.array_equal(gv, vc)       # reading never writes
 
 
+@pytest.mark.parametrize("d", [64, 128])             # 128-channel heads always append by a launch of their own
 @pytest.mark.parametrize("way", ["in_kernel", "own_launch"])
 @pytest.mark.parametrize("split_tokens", [0, 64])
-def test_fused_append_skips_tokens_it_cannot_place(way, split_tokens, launch_override):
+def test_fused_append_skips_tokens_it_cannot_place(way, split_tokens, d, launch_override):
     launch_override("append_fused", 1 if way == "in_kernel" else 0)
-    case = wl.make_case("hf", B=5, Hq=8, Hkv=2, d=64, P=16, seq_lens=[300, 517, 130, 260, 33], seed=91)
+    case = wl.make_case("hf", B=5, Hq=8, Hkv=2, d=d, P=16, seq_lens=[300, 517, 130, 260, 33], seed=91)
     last = case.offsets[1:] - 1
     prefix = case.slot_mapping.copy()
     prefix[last] = -1
@@ -111,10 +113,10 @@ def test_fused_append_skips_tokens_it_cannot_place(way, split_tokens, launch_ove
 
 
 @pytest.mark.parametrize("form", ["tile", "token"])
-@pytest.mark.parametrize("rope", [False, True])
-def test_append_skips_slots_outside_the_cache(form, rope, launch_override):
+@pytest.mark.parametrize("rope,d", [(False, 64), (True, 64), (False, 128)])
+def test_append_skips_slots_outside_the_cache(form, rope, d, launch_override):
     launch_override("append_form", pz.APPEND_FORM_TOKEN if form == "token" else pz.APPEND_FORM_TILE)
-    Hkv, d, P, T, num_pages = 2, 64, 16, 150, 12
+    Hkv, P, T, num_pages = 2, 16, 150, 12
     rng = np.random.default_rng(5)
     k = wl.bf16_bits(rng.standard_normal((T, Hkv, d)).astype(np.float32))
     v = wl.bf16_bits(rng.standard_normal((T, Hkv, d)).astype(np.float32))

@@ -60,6 +60,22 @@ def test_append_and_decode_beyond_4_gib(kv_dtype):
         assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL, (window, split)
 
 
+def test_128_channel_heads_beyond_4_gib():
+    case = wl.make_case("big128", B=3, Hq=16, Hkv=4, d=128, P=64, seq_lens=[3000, 700, 65], seed=42)
+    big, shift = lifted(case)
+    cache = gpu_cache(big)
+    gk, gv = to_oracle_layout(top_pages(cache, shift))
+    ok, ov = oracle_cache(case)
+    assert np.array_equal(gk, ok) and np.array_equal(gv, ov)
+    assert untouched_below(cache, shift, 0xAA)
+    for window, split in ((0, 0), (0, 256), (500, 256)):
+        want = oracle.decode_attn(ok, ov, case.P, case.q, case.block_table, case.seq_lens, sinks=case.sinks,
+                                  sm_scale=case.sm_scale, k_scale=case.k_scale, v_scale=case.v_scale, window=window,
+                                  nthreads=8)
+        got = gpu_attn(big, cache, window=window, split_tokens=split)
+        assert not np.any(np.isnan(got)) and rel_err(got, want) <= TOL, (window, split)
+
+
 def test_fused_append_rotary_append_and_prefill_beyond_4_gib():
     case = wl.make_case("big2", B=2, Hq=16, Hkv=8, d=64, P=64, seq_lens=[900, 130], seed=41)
     big, shift = lifted(case)
