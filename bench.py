@@ -18,7 +18,7 @@ taken from the very kernel sources that are running), `cpu_baseline` (the CPU or
 same workload, with a parity figure), `bf16_kv`, `repetitions`, `fused_append`, `stream_read`,
 `hip_graph`, `tuned_split`, and `all_configs`: the other benchmark configurations (cfg2, cfg4 at
 window 128 and 8192, the 36-layer cfg5 step) and the widened rows (max calibration, prefill, the
-window page pool, the fused rotary append), each run through the same code as `--workload NAME` with
+window page pool, the fused rotary append, 128-channel heads), each run through the same code as `--workload NAME` with
 fewer repetitions and reported as step time, kernel fraction of its roofline and oracle parity.
 """
 from __future__ import annotations
@@ -85,7 +85,7 @@ WORKLOADS = {
 }
 OTHER_WORKLOADS = ["cfg5", "calib", "prefill", "pool", "rope"]
 # what the default run reports besides the headline, in this order
-ALL_CONFIGS = ["cfg2", "cfg4_w128", "cfg4_w8192", "cfg5", "calib", "prefill", "pool", "rope"]
+ALL_CONFIGS = ["cfg2", "cfg4_w128", "cfg4_w8192", "cfg5", "calib", "prefill", "pool", "rope", "diag_d128"]
 
 # Sources that decide what the decode-attention launches do.  The HBM-traffic figure in profiles/ was
 # measured with hardware counters on a build of exactly these bytes; the summary records their hash.
