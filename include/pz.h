@@ -244,7 +244,7 @@ pz_status pz_decode_attn_splitk_reduce(const void *workspace, size_t workspace_b
  * every GPU the library runs on from the load of its code until the process ends); its address on the
  * current device is looked up at the first call with that device current (make that call outside a
  * capture) and kept.  Arguments and results exactly as the two calls with a workspace of
- * pz_decode_attn_workspace_bytes(batch, n_q_heads, 64, n_splits) bytes; `out` is written by this call.
+ * pz_decode_attn_workspace_bytes(batch, n_q_heads, head_dim, n_splits) bytes; `out` is written by this call.
  *   PZ_ERR_WORKSPACE   the partials of the call would not fit the array (nothing is enqueued)
  *   split_tokens == 0  single pass, no partials: the same as pz_decode_attn (n_splits ignored)
  * seq_lens is required (the merge uses only the rows this call wrote; what the array keeps from earlier
